@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: plan + forward + backward of packed
+varlen causal attention over one synthetic micro-batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+
+One "step" = skrull_attn_plan + skrull_attn_fwd + skrull_attn_bwd on the
+Llama-3-8B-shaped mixed-length micro-batch (config 3; 32,768 tokens: one
+24,576-token sequence + short ones).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line: useful causal TFLOP/s (14*A*d*Hq flops
+per step, A = attended pairs), a roofline object for the dominant kernel
+(timed live with HIP events on the launch stream) and the CPU oracle timed on
+a bounded sample of the same micro-batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def cpu_baseline(w, np):
+    """The fp64 oracle, as it stands, on a bounded sample: the local (short)
+    sequences of the micro-batch, all heads, full forward + backward."""
+    import oracle
+    from paper_2505_19609_amd import workloads as W
+    keep = [k for k in range(len(w.seq_len)) if w.shard_degree[k] == 1 and w.seq_len[k] <= 8192]
+    # bound the sample to about 1.2e7 attended pairs (10-30 s of CPU work)
+    S, pairs = [], 0
+    for k in keep:
+        L = w.seq_len[k]
+        if pairs + L * (L + 1) // 2 > 1.2e7 and S:
+            continue
+        S.append(L)
+        pairs += L * (L + 1) // 2
+    desc = oracle.ranges(S)
+    sub = W.Workload("sample", S, [1] * len(S), [0] * len(S), w.num_q_heads, w.num_kv_heads,
+                     w.head_dim, w.softmax_scale, w.value_seed + 7)
+    vals = W.make_values(sub, desc["total_q"], desc["total_k"])
+    f = {n: W.bf16_bits_to_f32(a) for n, a in vals.items()}
+    t0 = time.perf_counter()
+    oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
+    oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
+    dt = time.perf_counter() - t0
+    useful = 14 * oracle.attended_pairs(desc) * w.head_dim * w.num_q_heads
+    return {"value": useful / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"{len(S)} short sequences of the micro-batch ({sum(S)} tokens, "
+                      f"{oracle.attended_pairs(desc)} pairs), all {w.num_q_heads} query heads, fp64 fwd+bwd"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="benchmark micro-batch 1..5 (default 3)")
+    ap.add_argument("--shard-index", type=int, default=None)
+    ap.add_argument("--block-m", type=int, default=0)
+    ap.add_argument("--block-n", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding across "
+              "GPUs); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2505_19609_amd import binding as B
+    from paper_2505_19609_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = W.config(args.config, args.shard_index) if args.config in (4, 5) else W.config(args.config)
+
+    def make_plan():
+        return B.skrull_attn_plan(w.seq_len, w.shard_degree, w.shard_index, w.num_q_heads,
+                                  w.num_kv_heads, w.head_dim, w.softmax_scale, args.block_m,
+                                  args.block_n)
+
+    plan = make_plan()
+    Tq, Tk, Hq, Hkv, d = plan.total_q, plan.total_k, w.num_q_heads, w.num_kv_heads, w.head_dim
+    # synthetic N(0,1) bf16 tensors drawn on the device (values do not affect cost)
+    gen = torch.Generator(device="cuda").manual_seed(w.value_seed)
+    q = torch.randn((Tq, Hq, d), generator=gen, device="cuda", dtype=torch.float32).mul_(w.q_prescale).bfloat16()
+    k = torch.randn((Tk, Hkv, d), generator=gen, device="cuda", dtype=torch.float32).bfloat16()
+    v = torch.randn((Tk, Hkv, d), generator=gen, device="cuda", dtype=torch.float32).bfloat16()
+    do = torch.randn((Tq, Hq, d), generator=gen, device="cuda", dtype=torch.float32).bfloat16()
+    o, dq = torch.empty_like(q), torch.empty_like(q)
+    dk, dv = torch.empty_like(k), torch.empty_like(v)
+    lse = torch.empty((Hq, Tq), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(int(plan.bwd_workspace_bytes), 16), dtype=torch.uint8, device="cuda")
+    pairs = int(plan.attended_pairs)
+    useful = int(plan.useful_flops_fwd + plan.useful_flops_bwd)
+    n_fwd_items, n_dkv_items = plan.n_fwd_items, plan.n_dkv_items
+    plan.destroy()
+
+    def step():
+        p = make_plan()
+        B.skrull_attn_fwd(p, q, k, v, o, lse)
+        B.skrull_attn_bwd(p, q, k, v, o, lse, do, dq, dk, dv, ws)
+        return p
+
+    for _ in range(args.warmup):
+        step().destroy()
+    torch.cuda.synchronize()
+
+    B.skrull_attn_profile(True)
+    kms = np.zeros(4)
+    t_plan = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tp = time.perf_counter()
+        p = make_plan()
+        t_plan += time.perf_counter() - tp
+        B.skrull_attn_fwd(p, q, k, v, o, lse)
+        B.skrull_attn_bwd(p, q, k, v, o, lse, do, dq, dk, dv, ws)
+        kms += np.array(B.skrull_attn_profile_read())  # waits for this step's kernels
+        p.destroy()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    B.skrull_attn_profile(False)
+    kms /= args.steps
+    ms_step = dt / args.steps * 1e3
+    tflops = useful / (dt / args.steps) / 1e12
+
+    # dominant kernel and its algorithmic flops per launch:
+    #   forward 4*A*d*Hq; dK/dV kernel 8*A*d*Hq (S, dP, dV, dK); dQ kernel 2*A*d*Hq
+    #   (its recomputation of S and dP is not algorithmic work)
+    unit = pairs * d * Hq
+    kernels = {"fwd_kernel": (kms[0], 4 * unit), "dkv_kernel": (kms[2], 8 * unit), "dq_kernel": (kms[3], 2 * unit)}
+    dom = max(kernels, key=lambda n: kernels[n][0])
+    ach = kernels[dom][1] / (kernels[dom][0] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "kernel_ms": {"fwd": round(float(kms[0]), 4), "delta": round(float(kms[1]), 4),
+                              "dkv": round(float(kms[2]), 4), "dq": round(float(kms[3]), 4)}}
+    out = {
+        "metric": "varlen causal attn fwd+bwd useful TFLOP/s, 1 GPU",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "config": {"workload": w.name, "num_seqs": len(w.seq_len), "total_q": Tq, "total_k": Tk,
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "attended_pairs": pairs,
+                   "useful_flops_per_step": useful, "block_m": args.block_m or 128,
+                   "block_n": args.block_n or 128, "fwd_items": n_fwd_items, "dkv_items": n_dkv_items,
+                   "step": "plan + fwd + bwd", "ms_plan": round(t_plan / args.steps * 1e3, 4)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, np)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,181 @@
+/*
+ * skrull_attn.h -- C ABI of the MI355X (gfx950) packed variable-length causal
+ * attention library: forward and backward over ONE scheduled micro-batch.
+ *
+ * The micro-batch is the paper's (Sec. 4.1, Eq. 1-8): context-parallel rank j
+ * holds every local sequence assigned to it whole (P_kj = 1) and a 1/N slice
+ * of every distributed sequence (D_k = 1; Eq. 8 charges S_k/N of its tokens to
+ * each rank).  The caller states it exactly that way: a list of full sequence
+ * lengths S[K], and per sequence a shard degree (1 = local, N = distributed)
+ * and the shard index this GPU holds.  Sequences are packed without padding
+ * (App. B.1) and never attend to one another.  A shard is the contiguous query
+ * range [floor(r*S/N), floor((r+1)*S/N)) attending to the gathered key/value
+ * prefix [0, q_end) at its true positions (the paper leaves the cut open; it
+ * only fixes the S/N token count).
+ *
+ * All tensors are caller-owned DEVICE memory, contiguous, 16-byte aligned,
+ * token-major with head_dim innermost:
+ *   Q, O, dQ, dO : bf16 [total_q, num_q_heads, head_dim]
+ *   K, V, dK, dV : bf16 [total_k, num_kv_heads, head_dim]
+ *   LSE          : fp32 [num_q_heads, total_q]   (natural log, scale included)
+ * Sequence k owns query rows cu_q[k]..cu_q[k+1]-1 and key/value rows
+ * cu_k[k]..cu_k[k+1]-1; the latter are key positions 0..kv_len[k]-1.
+ * Query head h reads key/value head h / (num_q_heads / num_kv_heads).
+ *
+ * Every function returns 0 (SKRULL_OK) or a negative code; nothing throws or
+ * aborts, and the only process-wide state is the opt-in profiling switch at
+ * the end of this header.  On failure output pointers written
+ * through `out` arguments are left untouched.  Every step runs in HIP kernels;
+ * there is no CPU fallback.
+ */
+#ifndef SKRULL_ATTN_H
+#define SKRULL_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SKRULL_OK            0
+#define SKRULL_EINVAL       (-1)  /* bad argument (see each function)            */
+#define SKRULL_ENOMEM       (-2)  /* host or device allocation failed            */
+#define SKRULL_EHIP         (-3)  /* a HIP runtime call failed                   */
+#define SKRULL_EUNSUPPORTED (-4)  /* no device, or the device is not gfx950      */
+
+typedef struct skrull_attn_plan skrull_attn_plan_t; /* opaque, library-owned */
+
+/* The problem, in the paper's terms (Alg. 1 inputs S[K], N; Eq. 1-8 D_k, P_kj). */
+typedef struct {
+    int32_t        num_seqs;      /* K >= 1                                                   */
+    const int32_t *seq_len;       /* [K] HOST; full (unsharded) length S_k >= 1                */
+    const int32_t *shard_degree;  /* [K] HOST; 1 = local (D_k = 0), N > 1 = distributed; <= S_k */
+    const int32_t *shard_index;   /* [K] HOST; 0 <= index < degree                             */
+    int32_t        num_q_heads;   /* Hq >= 1                                                   */
+    int32_t        num_kv_heads;  /* Hkv >= 1, Hq % Hkv == 0                                   */
+    int32_t        head_dim;      /* 64 or 128                                                 */
+    float          softmax_scale; /* finite, > 0; multiplies Q.K^T inside the kernels          */
+    int32_t        block_m;       /* query rows per work item: 64, 128 or 256; 0 = 128          */
+    int32_t        block_n;       /* key rows per dK/dV work item: 64, 128 or 256; 0 = 128      */
+} skrull_attn_problem_t;
+
+typedef struct {
+    int32_t num_seqs, num_q_heads, num_kv_heads, head_dim;
+    int32_t block_m, block_n;
+    int32_t total_q;              /* sum of q_len  = rows of Q/O/dQ/dO                         */
+    int32_t total_k;              /* sum of kv_len = rows of K/V/dK/dV                         */
+    int32_t n_fwd_items;          /* entries of the forward / dQ work list                     */
+    int32_t n_dkv_items;          /* entries of the dK/dV work list                            */
+    int64_t attended_pairs;       /* exact number of (query, key) pairs under the causal mask  */
+    int64_t useful_flops_fwd;     /*  4 * pairs * head_dim * Hq                                */
+    int64_t useful_flops_bwd;     /* 10 * pairs * head_dim * Hq                                */
+    int64_t bwd_workspace_bytes;  /* device scratch skrull_attn_bwd needs (>= 0)               */
+} skrull_attn_plan_info_t;
+
+/* Arrays a plan holds on the device, for skrull_attn_plan_export. */
+enum {
+    SKRULL_ARRAY_CU_Q      = 0,   /* int32 [K+1]  exclusive prefix sums of q_len               */
+    SKRULL_ARRAY_CU_K      = 1,   /* int32 [K+1]  exclusive prefix sums of kv_len              */
+    SKRULL_ARRAY_Q_BEGIN   = 2,   /* int32 [K]    global position of the first local query     */
+    SKRULL_ARRAY_Q_LEN     = 3,   /* int32 [K]                                                 */
+    SKRULL_ARRAY_KV_LEN    = 4,   /* int32 [K]                                                 */
+    SKRULL_ARRAY_FWD_ITEMS = 5,   /* int32 [n_fwd_items][4] = {seq, q_block, q_row, n_kv}      */
+    SKRULL_ARRAY_DKV_ITEMS = 6    /* int32 [n_dkv_items][4] = {seq, kv_block, m0, n_q}         */
+};
+
+/*
+ * Build the varlen descriptor and the two cost-ordered tile work lists on the
+ * device (paper Eq. 8 for the slice sizes; the ordering applies the paper's
+ * load-balance rule -- heaviest piece first to the least-loaded worker, Alg. 1
+ * argmin(L) and Alg. 2's FLOPs bin-packing -- to compute units: items are
+ * stably sorted by descending quadratic cost and dispatched in that order).
+ *
+ * Forward/dQ list: one item per (sequence, block of block_m query rows), cost
+ * n_kv = ceil((q_begin + last_row + 1) / block_n).  dK/dV list: one item per
+ * (sequence, block of block_n key rows), m0 = first query block that can see
+ * it, cost n_q = number of query blocks that do.  Ties keep (sequence, block)
+ * ascending order, so the layout is a pure function of the inputs.
+ *
+ * p and the three arrays it points to are HOST memory, read before return.
+ * `hip_stream` (a hipStream_t, may be NULL for the default stream) carries the
+ * kernels; the call synchronises that stream because the totals come back to
+ * the host.  *out receives a plan that must be released with
+ * skrull_attn_plan_destroy.  A plan is immutable and may be reused by any
+ * number of fwd/bwd calls on any stream of the same device.
+ * SKRULL_EINVAL: null pointer, K < 1, S_k < 1, degree < 1, index outside
+ * [0, degree), degree > S_k, Hq % Hkv != 0, head_dim not 64/128, a block size
+ * other than 0/64/128/256, scale not finite/positive, a total of 2^31 rows or
+ * more, or more than 2^20 work items in either list.
+ */
+int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_attn_plan_t **out);
+
+/* Totals of a plan (host struct filled; no device work). */
+int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_t *info);
+
+/*
+ * Copy one of the plan's device arrays to HOST memory `dst` (synchronous).
+ * `bytes` must equal the array's exact size in bytes, else SKRULL_EINVAL.
+ */
+int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst, size_t bytes);
+
+/*
+ * Forward: for every sequence k, query head h, local row i at global position
+ * p = q_begin[k] + i, with c = h / (Hq/Hkv):
+ *     s_j = softmax_scale * q_i . k_j  (j = 0..p),  LSE = log sum_j exp(s_j),
+ *     O_i = sum_j exp(s_j - LSE) v_j.
+ * This is the O(n^2)-compute / O(n)-memory attention the paper's cost model
+ * rests on (Sec. 4.2.1; App. B.2, the 4*b*h*S^2 term).  bf16 MFMA products,
+ * fp32 accumulation and softmax, O rounded to bf16 (nearest even), LSE fp32.
+ * q, k, v (read) and o, lse (written) are DEVICE pointers in the layout above.
+ * Only enqueues on `hip_stream`; never synchronises.
+ * SKRULL_EINVAL on a null or misaligned pointer.
+ */
+int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
+                    void *o, float *lse, void *hip_stream);
+
+/*
+ * Backward of the same function, given dO and the forward's O and LSE:
+ *     D_i   = dO_i . O_i
+ *     P_ij  = exp(softmax_scale * q_i . k_j - LSE_i),  dS_ij = P_ij (dO_i . v_j - D_i)
+ *     dQ_i  = softmax_scale * sum_j dS_ij k_j
+ *     dK_j  = softmax_scale * sum_{h in group} sum_i dS_ij q_i
+ *     dV_j  =                 sum_{h in group} sum_i P_ij dO_i
+ * dK/dV of a shard are this rank's partial sums over its own query rows for
+ * the whole prefix (a multi-GPU caller would reduce them across ranks; the
+ * paper's Eq. 3/Volume(S) is that exchange).  All outputs bf16, rounded once
+ * from fp32 accumulators; the group sum is done in registers (no atomics, so
+ * results are bit-reproducible).
+ * `workspace` is DEVICE scratch of at least info.bwd_workspace_bytes, 16-byte
+ * aligned; contents on entry are ignored and on exit unspecified.
+ * Only enqueues on `hip_stream`; never synchronises.
+ * SKRULL_EINVAL on a null or misaligned pointer or a workspace that is too small.
+ */
+int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
+                    const void *o, const float *lse, const void *d_o,
+                    void *dq, void *dk, void *dv,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Release a plan and its device arrays (NULL is ignored). */
+void skrull_attn_plan_destroy(skrull_attn_plan_t *plan);
+
+/* Static description of a return code; for SKRULL_EHIP the text of the last
+ * HIP error seen by the calling thread is appended. Never NULL. */
+const char *skrull_attn_strerror(int code);
+
+/*
+ * Measurement aid (not part of the method).  While enabled, skrull_attn_fwd and
+ * skrull_attn_bwd bracket each of their kernels with HIP events recorded on
+ * the caller's stream.  skrull_attn_profile_read waits for the events of the
+ * most recent forward and backward calls and returns the kernel durations in
+ * milliseconds: ms[0] forward, ms[1] D = rowsum(dO*O), ms[2] dK/dV, ms[3] dQ
+ * (an entry is -1 if that call has not been made since enabling).  One set of
+ * events per process: use from one thread, one stream at a time.
+ */
+int skrull_attn_profile(int enable);
+int skrull_attn_profile_read(float ms[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKRULL_ATTN_H */

@@ -1,0 +1,183 @@
+"""ctypes binding of libskrull_attn.so: same names as the C ABI, argument
+marshalling only.  Tensors are torch CUDA(HIP) tensors used purely as device
+memory; every step of the path runs in the library's kernels.  There is no CPU
+fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libskrull_attn.so")
+
+SKRULL_OK, SKRULL_EINVAL, SKRULL_ENOMEM, SKRULL_EHIP, SKRULL_EUNSUPPORTED = 0, -1, -2, -3, -4
+ARRAY_CU_Q, ARRAY_CU_K, ARRAY_Q_BEGIN, ARRAY_Q_LEN, ARRAY_KV_LEN, ARRAY_FWD_ITEMS, ARRAY_DKV_ITEMS = range(7)
+
+EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
+                    "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_plan_destroy",
+                    "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read")
+
+
+class Problem(ctypes.Structure):
+    _fields_ = [("num_seqs", ctypes.c_int32),
+                ("seq_len", ctypes.POINTER(ctypes.c_int32)),
+                ("shard_degree", ctypes.POINTER(ctypes.c_int32)),
+                ("shard_index", ctypes.POINTER(ctypes.c_int32)),
+                ("num_q_heads", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float),
+                ("block_m", ctypes.c_int32),
+                ("block_n", ctypes.c_int32)]
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("num_seqs", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("block_m", ctypes.c_int32), ("block_n", ctypes.c_int32),
+                ("total_q", ctypes.c_int32), ("total_k", ctypes.c_int32),
+                ("n_fwd_items", ctypes.c_int32), ("n_dkv_items", ctypes.c_int32),
+                ("attended_pairs", ctypes.c_int64), ("useful_flops_fwd", ctypes.c_int64),
+                ("useful_flops_bwd", ctypes.c_int64), ("bwd_workspace_bytes", ctypes.c_int64)]
+
+
+class SkrullError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"skrull_attn error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load the in-tree HIP library; raise loudly if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run __graft_entry__.build() "
+                               "(python -m paper_2505_19609_amd.build); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        L.skrull_attn_plan.argtypes = [ctypes.POINTER(Problem), vp, ctypes.POINTER(vp)]
+        L.skrull_attn_plan.restype = ctypes.c_int
+        L.skrull_attn_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+        L.skrull_attn_plan_info.restype = ctypes.c_int
+        L.skrull_attn_plan_export.argtypes = [vp, ctypes.c_int, vp, ctypes.c_size_t]
+        L.skrull_attn_plan_export.restype = ctypes.c_int
+        L.skrull_attn_fwd.argtypes = [vp] * 7
+        L.skrull_attn_fwd.restype = ctypes.c_int
+        L.skrull_attn_bwd.argtypes = [vp] * 11 + [ctypes.c_size_t, vp]
+        L.skrull_attn_bwd.restype = ctypes.c_int
+        L.skrull_attn_plan_destroy.argtypes = [vp]
+        L.skrull_attn_plan_destroy.restype = None
+        L.skrull_attn_strerror.argtypes = [ctypes.c_int]
+        L.skrull_attn_strerror.restype = ctypes.c_char_p
+        L.skrull_attn_profile.argtypes = [ctypes.c_int]
+        L.skrull_attn_profile.restype = ctypes.c_int
+        L.skrull_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
+        L.skrull_attn_profile_read.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def skrull_attn_strerror(code: int) -> str:
+    return lib().skrull_attn_strerror(code).decode()
+
+
+def _check(rc: int):
+    if rc != SKRULL_OK:
+        raise SkrullError(rc, skrull_attn_strerror(rc))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(int(getattr(stream, "cuda_stream", stream)))
+
+
+class Plan:
+    """Owner of a ``skrull_attn_plan_t*``."""
+
+    def __init__(self, handle, info: PlanInfo):
+        self.handle = handle
+        self.info = info
+
+    def __getattr__(self, name):
+        return getattr(self.info, name)
+
+    def destroy(self):
+        if self.handle:
+            lib().skrull_attn_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def skrull_attn_plan(seq_len, shard_degree, shard_index, num_q_heads, num_kv_heads, head_dim,
+                     softmax_scale, block_m=0, block_n=0, stream=None, raw_stream=None) -> Plan:
+    S = np.ascontiguousarray(seq_len, dtype=np.int32)
+    N = np.ascontiguousarray(shard_degree, dtype=np.int32)
+    R = np.ascontiguousarray(shard_index, dtype=np.int32)
+    if not (S.shape == N.shape == R.shape and S.ndim == 1):
+        raise SkrullError(SKRULL_EINVAL, "seq_len / shard_degree / shard_index must be 1-D and equally long")
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    prob = Problem(int(S.shape[0]), S.ctypes.data_as(i32p), N.ctypes.data_as(i32p),
+                   R.ctypes.data_as(i32p), num_q_heads, num_kv_heads, head_dim,
+                   float(softmax_scale), block_m, block_n)
+    handle = ctypes.c_void_p()
+    st = ctypes.c_void_p(raw_stream) if raw_stream is not None else _stream_ptr(stream)
+    _check(lib().skrull_attn_plan(ctypes.byref(prob), st, ctypes.byref(handle)))
+    info = PlanInfo()
+    _check(lib().skrull_attn_plan_info(handle, ctypes.byref(info)))
+    return Plan(handle, info)
+
+
+def skrull_attn_plan_info(plan: Plan) -> PlanInfo:
+    info = PlanInfo()
+    _check(lib().skrull_attn_plan_info(plan.handle, ctypes.byref(info)))
+    return info
+
+
+def skrull_attn_plan_export(plan: Plan, which: int) -> np.ndarray:
+    K = plan.info.num_seqs
+    shape = {ARRAY_CU_Q: (K + 1,), ARRAY_CU_K: (K + 1,), ARRAY_Q_BEGIN: (K,), ARRAY_Q_LEN: (K,),
+             ARRAY_KV_LEN: (K,), ARRAY_FWD_ITEMS: (plan.info.n_fwd_items, 4),
+             ARRAY_DKV_ITEMS: (plan.info.n_dkv_items, 4)}[which]
+    out = np.zeros(shape, np.int32)
+    _check(lib().skrull_attn_plan_export(plan.handle, which, out.ctypes.data_as(ctypes.c_void_p),
+                                         out.nbytes))
+    return out
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def skrull_attn_fwd(plan: Plan, q, k, v, o, lse, stream=None):
+    _check(lib().skrull_attn_fwd(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                 _stream_ptr(stream)))
+
+
+def skrull_attn_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, stream=None):
+    _check(lib().skrull_attn_bwd(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                 _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def skrull_attn_profile(enable: bool):
+    _check(lib().skrull_attn_profile(int(bool(enable))))
+
+
+def skrull_attn_profile_read():
+    """Kernel durations (ms) of the last forward / backward: [fwd, delta, dkv, dq]."""
+    ms = (ctypes.c_float * 4)()
+    _check(lib().skrull_attn_profile_read(ms))
+    return [float(x) for x in ms]

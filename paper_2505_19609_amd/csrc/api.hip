@@ -1,0 +1,280 @@
+// Host side of the C ABI: argument validation, plan construction, launches.
+// No arithmetic of the method happens here; the descriptor, the work lists and
+// all attention math are produced by kernels (plan.hip, fwd.hip, bwd.hip).
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_err, sizeof g_err, "%s: %s", what, hipGetErrorString(e));
+    return e == hipErrorOutOfMemory ? SKRULL_ENOMEM : SKRULL_EHIP;
+}
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) { rc = hip_fail(e_, #expr); goto done; } \
+    } while (0)
+
+inline bool misaligned(const void *p) { return p == nullptr || ((uintptr_t)p & 15u) != 0; }
+
+inline int64_t align4(int64_t n) { return (n + 3) & ~(int64_t)3; }
+
+// Opt-in kernel timing: events 0/1 bracket the forward kernel, 2..5 delimit the
+// three backward kernels.
+bool g_profile = false;
+hipEvent_t g_ev[6];
+bool g_ev_made = false, g_fwd_seen = false, g_bwd_seen = false;
+
+constexpr int32_t kMaxItems = 1 << 20;  // rank-counting sort is quadratic in the item count
+
+int check_device(int *dev_out)
+{
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return SKRULL_EUNSUPPORTED;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SKRULL_EUNSUPPORTED;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return SKRULL_EUNSUPPORTED;
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return SKRULL_EUNSUPPORTED;
+    *dev_out = dev;
+    return SKRULL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_attn_plan_t **out)
+{
+    if (!p || !out || !p->seq_len || !p->shard_degree || !p->shard_index) return SKRULL_EINVAL;
+    const int32_t K = p->num_seqs;
+    if (K < 1) return SKRULL_EINVAL;
+    if (p->num_q_heads < 1 || p->num_kv_heads < 1 || p->num_q_heads % p->num_kv_heads != 0)
+        return SKRULL_EINVAL;
+    if (p->head_dim != 64 && p->head_dim != 128) return SKRULL_EINVAL;
+    if (!(p->softmax_scale > 0.0f) || !isfinite(p->softmax_scale)) return SKRULL_EINVAL;
+    const int32_t BM = p->block_m == 0 ? 128 : p->block_m;
+    const int32_t BN = p->block_n == 0 ? 128 : p->block_n;
+    if ((BM != 64 && BM != 128 && BM != 256) || (BN != 64 && BN != 128 && BN != 256))
+        return SKRULL_EINVAL;
+    // Entry checks that need no arithmetic are done here so that they work
+    // without a device; the kernel repeats them next to the range computation.
+    for (int32_t k = 0; k < K; ++k) {
+        const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
+        if (s < 1 || n < 1 || r < 0 || r >= n || n > s) return SKRULL_EINVAL;
+    }
+    int dev = 0;
+    int rc = check_device(&dev);
+    if (rc != SKRULL_OK) return rc;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    skrull_attn_plan_t *plan = nullptr;
+    int32_t *tmp = nullptr, *scratch = nullptr;
+    PlanTotals *totals_d = nullptr;
+    PlanTotals totals;
+    // tmp: S, N, R [K each], fwd_off, dkv_off [K+1 each]
+    const int64_t kpad = align4(K + 1);
+    const int64_t desc_ints = 5 * kpad;
+
+    plan = new (std::nothrow) skrull_attn_plan_t();
+    if (!plan) return SKRULL_ENOMEM;
+    memset(plan, 0, sizeof *plan);
+    plan->K = K; plan->Hq = p->num_q_heads; plan->Hkv = p->num_kv_heads; plan->d = p->head_dim;
+    plan->BM = BM; plan->BN = BN; plan->scale = p->softmax_scale; plan->device = dev;
+
+    HIP_TRY(hipMalloc((void **)&tmp, (size_t)(5 * kpad) * sizeof(int32_t)));
+    HIP_TRY(hipMalloc((void **)&totals_d, sizeof(PlanTotals)));
+    HIP_TRY(hipMalloc((void **)&plan->pool, (size_t)desc_ints * sizeof(int32_t)));
+    plan->cu_q = plan->pool;
+    plan->cu_k = plan->pool + kpad;
+    plan->q_begin = plan->pool + 2 * kpad;
+    plan->q_len = plan->pool + 3 * kpad;
+    plan->kv_len = plan->pool + 4 * kpad;
+    HIP_TRY(hipMemcpyAsync(tmp, p->seq_len, (size_t)K * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(tmp + kpad, p->shard_degree, (size_t)K * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(tmp + 2 * kpad, p->shard_index, (size_t)K * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_plan_ranges(tmp, tmp + kpad, tmp + 2 * kpad, K, BM, BN, plan->q_begin,
+                               plan->q_len, plan->kv_len, plan->cu_q, plan->cu_k, tmp + 3 * kpad,
+                               tmp + 4 * kpad, totals_d, st));
+    HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (totals.bad_entry != 0 || totals.total_q > INT32_MAX || totals.total_k > INT32_MAX ||
+        totals.n_fwd > kMaxItems || totals.n_dkv > kMaxItems) {
+        snprintf(g_err, sizeof g_err, "micro-batch too large or invalid entry %d", totals.bad_entry - 1);
+        rc = SKRULL_EINVAL;
+        goto done;
+    }
+    plan->total_q = (int32_t)totals.total_q;
+    plan->total_k = (int32_t)totals.total_k;
+    plan->n_fwd = (int32_t)totals.n_fwd;
+    plan->n_dkv = (int32_t)totals.n_dkv;
+    plan->pairs = totals.pairs;
+    {
+        const size_t item_bytes = (size_t)(plan->n_fwd + plan->n_dkv) * 16;
+        HIP_TRY(hipMalloc((void **)&plan->fwd_items, item_bytes));
+        plan->dkv_items = plan->fwd_items + 4 * (int64_t)plan->n_fwd;
+        HIP_TRY(hipMalloc((void **)&scratch, item_bytes));
+        HIP_TRY(launch_plan_items(plan, tmp + 3 * kpad, tmp + 4 * kpad, scratch,
+                                  scratch + 4 * (int64_t)plan->n_fwd, st));
+        HIP_TRY(hipStreamSynchronize(st));
+    }
+    rc = SKRULL_OK;
+done:
+    if (tmp) (void)hipFree(tmp);
+    if (totals_d) (void)hipFree(totals_d);
+    if (scratch) (void)hipFree(scratch);
+    if (rc != SKRULL_OK) {
+        if (plan) {
+            if (plan->pool) (void)hipFree(plan->pool);
+            if (plan->fwd_items) (void)hipFree(plan->fwd_items);
+            delete plan;
+        }
+        return rc;
+    }
+    *out = plan;
+    return SKRULL_OK;
+}
+
+int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_t *info)
+{
+    if (!plan || !info) return SKRULL_EINVAL;
+    info->num_seqs = plan->K;
+    info->num_q_heads = plan->Hq;
+    info->num_kv_heads = plan->Hkv;
+    info->head_dim = plan->d;
+    info->block_m = plan->BM;
+    info->block_n = plan->BN;
+    info->total_q = plan->total_q;
+    info->total_k = plan->total_k;
+    info->n_fwd_items = plan->n_fwd;
+    info->n_dkv_items = plan->n_dkv;
+    info->attended_pairs = plan->pairs;
+    info->useful_flops_fwd = 4 * plan->pairs * plan->d * plan->Hq;
+    info->useful_flops_bwd = 10 * plan->pairs * plan->d * plan->Hq;
+    info->bwd_workspace_bytes = (((int64_t)plan->Hq * plan->total_q * 4) + 255) & ~(int64_t)255;
+    return SKRULL_OK;
+}
+
+int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst, size_t bytes)
+{
+    if (!plan || !dst) return SKRULL_EINVAL;
+    const int32_t *src = nullptr;
+    size_t n = 0;
+    switch (which) {
+    case SKRULL_ARRAY_CU_Q: src = plan->cu_q; n = (size_t)plan->K + 1; break;
+    case SKRULL_ARRAY_CU_K: src = plan->cu_k; n = (size_t)plan->K + 1; break;
+    case SKRULL_ARRAY_Q_BEGIN: src = plan->q_begin; n = (size_t)plan->K; break;
+    case SKRULL_ARRAY_Q_LEN: src = plan->q_len; n = (size_t)plan->K; break;
+    case SKRULL_ARRAY_KV_LEN: src = plan->kv_len; n = (size_t)plan->K; break;
+    case SKRULL_ARRAY_FWD_ITEMS: src = plan->fwd_items; n = (size_t)plan->n_fwd * 4; break;
+    case SKRULL_ARRAY_DKV_ITEMS: src = plan->dkv_items; n = (size_t)plan->n_dkv * 4; break;
+    default: return SKRULL_EINVAL;
+    }
+    if (bytes != n * sizeof(int32_t)) return SKRULL_EINVAL;
+    hipError_t e = hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy(export)");
+    return SKRULL_OK;
+}
+
+int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
+                    void *o, float *lse, void *hip_stream)
+{
+    if (!plan) return SKRULL_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
+        return SKRULL_EINVAL;
+    if (g_profile) (void)hipEventRecord(g_ev[0], (hipStream_t)hip_stream);
+    hipError_t e = launch_fwd(plan, q, k, v, o, lse, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "forward launch");
+    if (g_profile) { (void)hipEventRecord(g_ev[1], (hipStream_t)hip_stream); g_fwd_seen = true; }
+    return SKRULL_OK;
+}
+
+int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
+                    const void *o, const float *lse, const void *d_o, void *dq, void *dk, void *dv,
+                    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!plan) return SKRULL_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+        misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
+        misaligned(workspace))
+        return SKRULL_EINVAL;
+    skrull_attn_plan_info_t info;
+    skrull_attn_plan_info(plan, &info);
+    if ((int64_t)workspace_bytes < info.bwd_workspace_bytes) return SKRULL_EINVAL;
+    hipError_t e = launch_bwd(plan, q, k, v, o, lse, d_o, dq, dk, dv, (float *)workspace,
+                              (hipStream_t)hip_stream, g_profile ? g_ev + 2 : nullptr);
+    if (e != hipSuccess) return hip_fail(e, "backward launch");
+    if (g_profile) g_bwd_seen = true;
+    return SKRULL_OK;
+}
+
+void skrull_attn_plan_destroy(skrull_attn_plan_t *plan)
+{
+    if (!plan) return;
+    if (plan->pool) (void)hipFree(plan->pool);
+    if (plan->fwd_items) (void)hipFree(plan->fwd_items);
+    delete plan;
+}
+
+int skrull_attn_profile(int enable)
+{
+    if (enable && !g_ev_made) {
+        for (int i = 0; i < 6; ++i) {
+            hipError_t e = hipEventCreate(&g_ev[i]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+        }
+        g_ev_made = true;
+    }
+    g_profile = enable != 0;
+    g_fwd_seen = g_bwd_seen = false;
+    return SKRULL_OK;
+}
+
+int skrull_attn_profile_read(float ms[4])
+{
+    if (!ms || !g_ev_made) return SKRULL_EINVAL;
+    for (int i = 0; i < 4; ++i) ms[i] = -1.0f;
+    hipError_t e;
+    if (g_fwd_seen) {
+        if ((e = hipEventSynchronize(g_ev[1])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        if ((e = hipEventElapsedTime(&ms[0], g_ev[0], g_ev[1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+    }
+    if (g_bwd_seen) {
+        if ((e = hipEventSynchronize(g_ev[5])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        for (int i = 0; i < 3; ++i)
+            if ((e = hipEventElapsedTime(&ms[1 + i], g_ev[2 + i], g_ev[3 + i])) != hipSuccess)
+                return hip_fail(e, "hipEventElapsedTime");
+    }
+    return SKRULL_OK;
+}
+
+const char *skrull_attn_strerror(int code)
+{
+    thread_local char buf[320];
+    switch (code) {
+    case SKRULL_OK: return "ok";
+    case SKRULL_EINVAL:
+        if (g_err[0]) { snprintf(buf, sizeof buf, "invalid argument (%s)", g_err); return buf; }
+        return "invalid argument";
+    case SKRULL_ENOMEM: return "out of memory";
+    case SKRULL_EHIP: snprintf(buf, sizeof buf, "HIP runtime error (%s)", g_err); return buf;
+    case SKRULL_EUNSUPPORTED: return "no gfx950 (MI355X) device available";
+    default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,360 @@
+// Backward kernels: D = rowsum(dO * O), dQ, and dK/dV with the GQA head
+// reduction, for the packed varlen causal attention of fwd.hip.
+//
+//   P_ij  = exp(scale * q_i.k_j - LSE_i)          dP_ij = dO_i . v_j
+//   dS_ij = P_ij (dP_ij - D_i)
+//   dQ_i  = scale * sum_j dS_ij k_j
+//   dK_j  = scale * sum_{h in group} sum_i dS_ij q_i
+//   dV_j  =         sum_{h in group} sum_i P_ij dO_i
+//
+// dQ kernel: work items and orientation of the forward kernel (query index on
+// the MFMA column, so LSE_i and D_i are per-lane scalars):
+//     S^T = K Q^T, dP^T = V dO^T           A = K / V tile rows (LDS), B = Q / dO (registers)
+//     dQ^T[t,i] += sum_j K^T[t,j] dS^T[j,i] A = transposed K tile (LDS), B = dS^T (registers)
+// dK/dV kernel: one workgroup owns BN key rows of one KV head and walks over
+// the g query heads of the group and the query tiles that can see them; the
+// key index is on the MFMA column, so the two accumulators of a lane belong to
+// one key row and the group sum never leaves registers:
+//     S = Q K^T, dP = dO V^T               A = Q / dO tile rows (LDS), B = K / V (registers)
+//     dV^T[t,j] += sum_i dO^T[t,i] P[i,j]   A = transposed dO tile (LDS), B = P (registers)
+//     dK^T[t,j] += sum_i Q^T[t,i] dS[i,j]   A = transposed Q tile (LDS),  B = dS (registers)
+// The paper's FLOPs model counts this quadratic work per sequence (App. B.2);
+// the work-list order balances it over compute units (plan.hip).
+#include "common.h"
+#include "mfma.h"
+#include "tiles.h"
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------
+// D[h, row] = sum_t dO[row,h,t] * O[row,h,t]
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void delta_kernel(const uint16_t *__restrict__ o,
+                                                    const uint16_t *__restrict__ d_o,
+                                                    float *__restrict__ delta, int64_t n_pairs,
+                                                    int32_t Hq, int32_t total_q)
+{
+    constexpr int CH = D / 8;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t pair = gid / CH;  // (row, head) flattened row-major
+    float acc = 0.0f;
+    if (pair < n_pairs) {
+        const uint4 a = *(const uint4 *)(o + gid * 8);
+        const uint4 b = *(const uint4 *)(d_o + gid * 8);
+        const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            acc += __builtin_bit_cast(float, aw[w] << 16) * __builtin_bit_cast(float, bw[w] << 16);
+            acc += __builtin_bit_cast(float, aw[w] & 0xffff0000u) *
+                   __builtin_bit_cast(float, bw[w] & 0xffff0000u);
+        }
+    }
+#pragma unroll
+    for (int off = CH / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (pair < n_pairs && (gid % CH) == 0) {
+        const int64_t row = pair / Hq;
+        const int32_t hh = (int32_t)(pair % Hq);
+        delta[(int64_t)hh * total_q + row] = acc;
+    }
+}
+
+struct BwdParams {
+    const uint16_t *q, *k, *v, *d_o;
+    const float *lse, *delta;
+    uint16_t *dq, *dk, *dv;
+    const int4 *fwd_items, *dkv_items;
+    const int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len;
+    int32_t Hq, Hkv, total_q, BM, BN;
+    float scale, scale_log2;
+};
+
+// ---------------------------------------------------------------------------
+// dQ
+// ---------------------------------------------------------------------------
+constexpr int NW = 4;          // wavefronts per workgroup
+constexpr int SUB = 32 * NW;   // query (dQ) or key (dK/dV) rows per pass
+
+template <int D>
+__global__ __launch_bounds__(64 * NW) void dq_kernel(const BwdParams prm)
+{
+    constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
+    __shared__ __align__(16) unsigned char lds_k[KT * D * 2];   // K rows
+    __shared__ __align__(16) unsigned char lds_v[KT * D * 2];   // V rows
+    __shared__ __align__(16) unsigned char lds_kt[D * KT * 2];  // K transposed
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int item_id = blockIdx.x / prm.Hq, hl = blockIdx.x % prm.Hq;
+    const int g = prm.Hq / prm.Hkv;
+    const int c = hl % prm.Hkv;
+    const int head = c * g + hl / prm.Hkv;
+
+    const int4 it = prm.fwd_items[item_id];
+    const int seq = it.x;
+    const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
+    const int kbase = prm.cu_k[seq];
+    const int item_rows = min(prm.BM, ql - it.y * prm.BM);
+
+    for (int sub = 0; sub * SUB < item_rows; ++sub) {
+    const int row0 = it.y * prm.BM + sub * SUB;
+    const int qrow0 = it.z + sub * SUB;
+    const int rows = min(SUB, ql - row0);
+    const int p0 = qb + row0;
+    const int n_tiles = (p0 + rows + KT - 1) / KT;
+
+    const int wrow0 = 32 * wave;
+    const bool wave_active = wrow0 < rows;
+    const int my_i = wrow0 + n;
+    const int my_pos = p0 + my_i;
+    const int w_pmin = p0 + wrow0;
+    const int w_pmax = p0 + min(wrow0 + 31, rows - 1);
+    const int my_row = qrow0 + min(my_i, rows - 1);  // packed row, clamped for loads
+
+    bf16x8 qf[KS], dof[KS];
+    {
+        const size_t off = ((size_t)my_row * prm.Hq + head) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = as_bf16x8(*(const uint4 *)(prm.q + off + 16 * ks));
+            dof[ks] = as_bf16x8(*(const uint4 *)(prm.d_o + off + 16 * ks));
+        }
+    }
+    const float lse2 = prm.lse[(size_t)head * prm.total_q + my_row] * kLog2e;
+    const float dlt = prm.delta[(size_t)head * prm.total_q + my_row];
+
+    QuadStage<D, NT> kst, vst;
+    const size_t kv_stride = (size_t)prm.Hkv * D;
+    const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + c) * D;
+    const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + c) * D;
+
+    f32x16 acc[TT];
+    zero_acc(acc);
+    const float cs = prm.scale_log2;
+
+    kst.load(kp, kv_stride, 0, kvl - 1, tid);
+    vst.load(vp, kv_stride, 0, kvl - 1, tid);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int kv0 = tile * KT;
+        __syncthreads();
+        kst.store_rm(lds_k, tid);
+        kst.store_tr(lds_kt, tid);
+        vst.store_rm(lds_v, tid);
+        __syncthreads();
+        if (tile + 1 < n_tiles) {
+            kst.load(kp, kv_stride, kv0 + KT, kvl - 1, tid);
+            vst.load(vp, kv_stride, kv0 + KT, kvl - 1, tid);
+        }
+        if (wave_active && kv0 <= w_pmax) {
+            f32x16 s[2], dp[2];
+            zero_acc(s);
+            zero_acc(dp);
+#pragma unroll
+            for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    s[jt] = mfma32(frag_rm<CH>(lds_k, 32 * jt + n, ks, h), qf[ks], s[jt]);
+                    dp[jt] = mfma32(frag_rm<CH>(lds_v, 32 * jt + n, ks, h), dof[ks], dp[jt]);
+                }
+            const bool diag = kv0 + KT - 1 > w_pmin;
+#pragma unroll
+            for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float p = fast_exp2(__builtin_fmaf(s[jt][v], cs, -lse2));
+                    if (diag && kv0 + 32 * jt + acc_row(v, h) > my_pos) p = 0.0f;
+                    s[jt][v] = p * (dp[jt][v] - dlt);  // dS^T
+                }
+#pragma unroll
+            for (int kbg = 0; kbg < 4; ++kbg) {
+                const bf16x8 ds = acc_to_b(s[kbg >> 1], kbg & 1);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc[tt] = mfma32(frag_tr(lds_kt, 32 * tt + n, kbg, h), ds, acc[tt]);
+            }
+        }
+    }
+    if (wave_active && my_i < rows)
+        store_rows_bf16<TT>(prm.dq + ((size_t)(qrow0 + my_i) * prm.Hq + head) * D, acc, prm.scale, h);
+    }  // pass
+}
+
+// ---------------------------------------------------------------------------
+// dK / dV
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64 * NW) void dkv_kernel(const BwdParams prm)
+{
+    constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, QT = TILE_ROWS;
+    __shared__ __align__(16) unsigned char lds_q[QT * D * 2];    // Q rows
+    __shared__ __align__(16) unsigned char lds_do[QT * D * 2];   // dO rows
+    __shared__ __align__(16) unsigned char lds_qt[D * QT * 2];   // Q transposed
+    __shared__ __align__(16) unsigned char lds_dot[D * QT * 2];  // dO transposed
+    __shared__ __align__(16) float lds_lse[QT];
+    __shared__ __align__(16) float lds_dlt[QT];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int item_id = blockIdx.x / prm.Hkv, c = blockIdx.x % prm.Hkv;
+    const int g = prm.Hq / prm.Hkv;
+
+    const int4 it = prm.dkv_items[item_id];
+    const int seq = it.x;
+    const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
+    const int kbase = prm.cu_k[seq], qbase = prm.cu_q[seq];
+    const int item_rows = min(prm.BN, kvl - it.y * prm.BN);
+
+    for (int sub = 0; sub * SUB < item_rows; ++sub) {
+    const int kv0 = it.y * prm.BN + sub * SUB;     // first key position of the pass
+    const int krows = min(SUB, kvl - kv0);
+
+    const int wj0 = kv0 + 32 * wave;               // this wave's first key position
+    const bool wave_active = 32 * wave < krows;
+    const int my_j = wj0 + n;                      // this lane's key position
+    const int my_krow = kbase + min(my_j, kvl - 1);
+
+    // K and V fragments of this lane's key row (B operands), kept for the whole kernel.
+    bf16x8 kf[KS], vf[KS];
+    {
+        const size_t off = ((size_t)my_krow * prm.Hkv + c) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = as_bf16x8(*(const uint4 *)(prm.k + off + 16 * ks));
+            vf[ks] = as_bf16x8(*(const uint4 *)(prm.v + off + 16 * ks));
+        }
+    }
+
+    // first local query row that can see key kv0, rounded down to a tile
+    const int i_first = (max(0, kv0 - qb) / QT) * QT;
+    const int n_qt = (ql - i_first + QT - 1) / QT;
+    const int n_iter = n_qt * g;
+
+    f32x16 dk[TT], dv[TT];
+    zero_acc(dk);
+    zero_acc(dv);
+    const float cs = prm.scale_log2;
+    const size_t q_stride = (size_t)prm.Hq * D;
+
+    QuadStage<D, NT> qst, dst;
+    float lse_st = 0.0f, dlt_st = 0.0f;  // staged by threads tid < QT
+
+    auto fetch = [&](int iter) __attribute__((always_inline)) {
+        const int head = c * g + iter / n_qt;
+        const int i0 = i_first + (iter % n_qt) * QT;
+        const uint16_t *qp = prm.q + ((size_t)qbase * prm.Hq + head) * D;
+        const uint16_t *dp = prm.d_o + ((size_t)qbase * prm.Hq + head) * D;
+        qst.load(qp, q_stride, i0, ql - 1, tid);
+        dst.load(dp, q_stride, i0, ql - 1, tid);
+        if (tid < QT) {
+            const int i = i0 + tid;
+            const size_t idx = (size_t)head * prm.total_q + qbase + min(i, ql - 1);
+            // rows past the end get LSE = +inf, which makes P (and dS) exactly zero
+            lse_st = (i < ql) ? prm.lse[idx] * kLog2e : INFINITY;
+            dlt_st = (i < ql) ? prm.delta[idx] : 0.0f;
+        }
+    };
+
+    if (n_iter > 0) fetch(0);
+    for (int iter = 0; iter < n_iter; ++iter) {
+        const int i0 = i_first + (iter % n_qt) * QT;
+        __syncthreads();
+        qst.store_rm(lds_q, tid);
+        qst.store_tr(lds_qt, tid);
+        dst.store_rm(lds_do, tid);
+        dst.store_tr(lds_dot, tid);
+        if (tid < QT) { lds_lse[tid] = lse_st; lds_dlt[tid] = dlt_st; }
+        __syncthreads();
+        if (iter + 1 < n_iter) fetch(iter + 1);
+
+        // skip tiles whose last query still precedes this wave's first key
+        if (wave_active && qb + i0 + QT - 1 >= wj0) {
+            const bool diag = qb + i0 < wj0 + 31;  // some (query, key) pair of the tile is masked
+#pragma unroll 1
+            for (int itile = 0; itile < 2; ++itile) {
+                f32x16 s, dp;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { s[v] = 0.0f; dp[v] = 0.0f; }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    s = mfma32(frag_rm<CH>(lds_q, 32 * itile + n, ks, h), kf[ks], s);
+                    dp = mfma32(frag_rm<CH>(lds_do, 32 * itile + n, ks, h), vf[ks], dp);
+                }
+#pragma unroll
+                for (int vb = 0; vb < 4; ++vb) {
+                    const int ib = 32 * itile + 8 * vb + 4 * h;  // 4 consecutive query rows
+                    const float4 l4 = *(const float4 *)(lds_lse + ib);
+                    const float4 d4 = *(const float4 *)(lds_dlt + ib);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = 4 * vb + e;
+                        float p = fast_exp2(__builtin_fmaf(s[v], cs, -lv[e]));
+                        if (diag && my_j > qb + i0 + ib + e) p = 0.0f;
+                        s[v] = p;                        // P
+                        dp[v] = p * (dp[v] - dvv[e]);    // dS
+                    }
+                }
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 pb = acc_to_b(s, kb), dsb = acc_to_b(dp, kb);
+                    const int kbg = 2 * itile + kb;
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        dv[tt] = mfma32(frag_tr(lds_dot, 32 * tt + n, kbg, h), pb, dv[tt]);
+                        dk[tt] = mfma32(frag_tr(lds_qt, 32 * tt + n, kbg, h), dsb, dk[tt]);
+                    }
+                }
+            }
+        }
+    }
+    if (wave_active && my_j < kvl) {
+        const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
+        store_rows_bf16<TT>(prm.dk + off, dk, prm.scale, h);
+        store_rows_bf16<TT>(prm.dv + off, dv, 1.0f, h);
+    }
+    }  // pass
+}
+
+template <int D>
+hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const void *o, float *delta,
+                    hipStream_t st, hipEvent_t *ev)
+{
+    if (ev) (void)hipEventRecord(ev[0], st);
+    const int64_t n_pairs = (int64_t)p->total_q * p->Hq;
+    const int64_t threads = n_pairs * (D / 8);
+    delta_kernel<D><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(
+        (const uint16_t *)o, prm.d_o, delta, n_pairs, p->Hq, p->total_q);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (ev) (void)hipEventRecord(ev[1], st);
+    const int gq = p->n_fwd * p->Hq, gk = p->n_dkv * p->Hkv;
+    dkv_kernel<D><<<gk, 64 * NW, 0, st>>>(prm);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (ev) (void)hipEventRecord(ev[2], st);
+    dq_kernel<D><<<gq, 64 * NW, 0, st>>>(prm);
+    if (ev) (void)hipEventRecord(ev[3], st);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,
+                      const void *o, const float *lse, const void *d_o, void *dq, void *dk,
+                      void *dv, float *delta, hipStream_t st, hipEvent_t *ev)
+{
+    BwdParams prm;
+    prm.q = (const uint16_t *)q; prm.k = (const uint16_t *)k; prm.v = (const uint16_t *)v;
+    prm.d_o = (const uint16_t *)d_o; prm.lse = lse; prm.delta = delta;
+    prm.dq = (uint16_t *)dq; prm.dk = (uint16_t *)dk; prm.dv = (uint16_t *)dv;
+    prm.fwd_items = (const int4 *)p->fwd_items; prm.dkv_items = (const int4 *)p->dkv_items;
+    prm.cu_q = p->cu_q; prm.cu_k = p->cu_k; prm.q_begin = p->q_begin; prm.q_len = p->q_len;
+    prm.kv_len = p->kv_len;
+    prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM; prm.BN = p->BN;
+    prm.scale = p->scale; prm.scale_log2 = p->scale * kLog2e;
+    if (p->d == 128) return launch_d<128>(p, prm, o, delta, st, ev);
+    if (p->d == 64) return launch_d<64>(p, prm, o, delta, st, ev);
+    return hipErrorInvalidValue;
+}

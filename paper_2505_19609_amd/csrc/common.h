@@ -1,0 +1,44 @@
+// Internal declarations shared by the HIP translation units of libskrull_attn.
+// Nothing here is part of the public ABI (that is include/skrull_attn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "skrull_attn.h"
+
+// Device-resident descriptor + work lists of one micro-batch.
+struct skrull_attn_plan {
+    int32_t K, Hq, Hkv, d, BM, BN;
+    float scale;
+    int32_t total_q, total_k, n_fwd, n_dkv;
+    int64_t pairs;
+    int device;
+    // one allocation; the pointers below index into it
+    int32_t *pool;
+    int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len;  // [K+1],[K+1],[K],[K],[K]
+    int32_t *fwd_items, *dkv_items;                   // [n][4], sorted
+};
+
+// Totals written by the ranges kernel and read back by the host.
+struct PlanTotals {
+    int64_t total_q, total_k, n_fwd, n_dkv, pairs;
+    int32_t bad_entry;   // index+1 of the first invalid sequence, 0 if none
+    int32_t pad;
+};
+
+// plan.hip
+hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r, int32_t K,
+                              int32_t BM, int32_t BN, int32_t *q_begin, int32_t *q_len,
+                              int32_t *kv_len, int32_t *cu_q, int32_t *cu_k, int32_t *fwd_off,
+                              int32_t *dkv_off, PlanTotals *totals, hipStream_t st);
+hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
+                             const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
+                             hipStream_t st);
+
+// fwd.hip / bwd.hip
+hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,
+                      void *o, float *lse, hipStream_t st);
+hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,
+                      const void *o, const float *lse, const void *d_o, void *dq, void *dk,
+                      void *dv, float *delta, hipStream_t st, hipEvent_t *ev);

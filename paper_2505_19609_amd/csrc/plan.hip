@@ -1,0 +1,199 @@
+// Varlen descriptor builder and cost-ordered tile work lists, on the device.
+//
+// The micro-batch is stated the way the paper states it (Sec. 4.1, Eq. 1-8):
+// full lengths S[K] plus, per sequence, local (degree 1) or distributed over N
+// ranks with this GPU holding slice `index` (Eq. 8: S_k/N tokens per rank).
+// Three small kernels:
+//   1. plan_ranges : per-sequence query/KV ranges, the packed offsets
+//                    (exclusive scans), per-sequence work-item offsets, totals
+//   2. plan_emit   : one thread per work item writes {seq, block, x, cost}
+//   3. plan_sort   : stable descending-cost order by rank counting, so the
+//                    hardware dispatcher, which hands out workgroups in grid
+//                    order, always gives the heaviest remaining tile to the
+//                    first compute unit that frees up -- the paper's
+//                    least-loaded-first rule (Alg. 1, argmin over L) applied
+//                    to compute units instead of ranks.
+#include "common.h"
+
+namespace {
+
+constexpr int kScanThreads = 256;
+
+// Block-wide exclusive scan of one int64 per thread; returns the exclusive
+// prefix and writes the block total to *total (same value in every thread).
+__device__ inline int64_t block_exclusive_scan(int64_t v, int64_t *lds, int64_t *total)
+{
+    const int t = threadIdx.x;
+    lds[t] = v;
+    __syncthreads();
+    for (int off = 1; off < kScanThreads; off <<= 1) {
+        int64_t add = (t >= off) ? lds[t - off] : 0;
+        __syncthreads();
+        lds[t] += add;
+        __syncthreads();
+    }
+    const int64_t incl = lds[t];
+    *total = lds[kScanThreads - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+__global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
+    const int32_t *__restrict__ S, const int32_t *__restrict__ N, const int32_t *__restrict__ R,
+    int32_t K, int32_t BM, int32_t BN, int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
+    int32_t *__restrict__ kv_len, int32_t *__restrict__ cu_q, int32_t *__restrict__ cu_k,
+    int32_t *__restrict__ fwd_off, int32_t *__restrict__ dkv_off, PlanTotals *__restrict__ totals)
+{
+    __shared__ int64_t lds[kScanThreads];
+    __shared__ int32_t first_bad;
+    const int t = threadIdx.x;
+    if (t == 0) first_bad = 0x7fffffff;
+    __syncthreads();
+    int64_t base_q = 0, base_k = 0, base_f = 0, base_d = 0, pairs = 0;
+    for (int32_t k0 = 0; k0 < K; k0 += kScanThreads) {
+        const int32_t k = k0 + t;
+        int64_t ql = 0, kl = 0, nf = 0, nd = 0, qb = 0, pr = 0;
+        if (k < K) {
+            const int64_t s = S[k], n = N[k], r = R[k];
+            if (s < 1 || n < 1 || r < 0 || r >= n || n > s) {
+                atomicMin(&first_bad, k);
+            } else {
+                qb = (r * s) / n;
+                kl = ((r + 1) * s) / n;
+                ql = kl - qb;
+                nf = ceil_div64(ql, BM);
+                nd = ceil_div64(kl, BN);
+                pr = (kl * (kl + 1) - qb * (qb + 1)) / 2;
+            }
+            q_begin[k] = (int32_t)qb;
+            q_len[k] = (int32_t)ql;
+            kv_len[k] = (int32_t)kl;
+        }
+        int64_t tot;
+        int64_t e = block_exclusive_scan(ql, lds, &tot);
+        if (k < K) cu_q[k] = (int32_t)(base_q + e);
+        base_q += tot;
+        e = block_exclusive_scan(kl, lds, &tot);
+        if (k < K) cu_k[k] = (int32_t)(base_k + e);
+        base_k += tot;
+        e = block_exclusive_scan(nf, lds, &tot);
+        if (k < K) fwd_off[k] = (int32_t)(base_f + e);
+        base_f += tot;
+        e = block_exclusive_scan(nd, lds, &tot);
+        if (k < K) dkv_off[k] = (int32_t)(base_d + e);
+        base_d += tot;
+        block_exclusive_scan(pr, lds, &tot);
+        pairs += tot;
+    }
+    __syncthreads();
+    if (t == 0) {
+        cu_q[K] = (int32_t)base_q;
+        cu_k[K] = (int32_t)base_k;
+        fwd_off[K] = (int32_t)base_f;
+        dkv_off[K] = (int32_t)base_d;
+        totals->total_q = base_q;
+        totals->total_k = base_k;
+        totals->n_fwd = base_f;
+        totals->n_dkv = base_d;
+        totals->pairs = pairs;
+        totals->bad_entry = (first_bad == 0x7fffffff) ? 0 : first_bad + 1;
+        totals->pad = 0;
+    }
+}
+
+// Largest k with off[k] <= item (off is an exclusive scan with off[K] = n).
+__device__ inline int32_t owner_of(const int32_t *off, int32_t K, int32_t item)
+{
+    int32_t lo = 0, hi = K;  // invariant: off[lo] <= item < off[hi]
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (off[mid] <= item) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void plan_emit_kernel(
+    int32_t K, int32_t BM, int32_t BN, const int32_t *__restrict__ q_begin,
+    const int32_t *__restrict__ q_len, const int32_t *__restrict__ kv_len,
+    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ fwd_off,
+    const int32_t *__restrict__ dkv_off, int32_t n_fwd, int32_t n_dkv,
+    int4 *__restrict__ fwd_items, int4 *__restrict__ dkv_items)
+{
+    const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n_fwd) {
+        const int32_t k = owner_of(fwd_off, K, t);
+        const int32_t m = t - fwd_off[k];
+        const int64_t row0 = (int64_t)m * BM;
+        const int64_t left = q_len[k] - row0;
+        const int64_t rows = left < BM ? left : BM;
+        fwd_items[t] = make_int4(k, m, (int32_t)(cu_q[k] + row0),
+                                 (int32_t)ceil_div64((int64_t)q_begin[k] + row0 + rows, BN));
+    }
+    if (t < n_dkv) {
+        const int32_t k = owner_of(dkv_off, K, t);
+        const int32_t b = t - dkv_off[k];
+        int64_t i0 = (int64_t)b * BN - q_begin[k];
+        if (i0 < 0) i0 = 0;
+        const int32_t m0 = (int32_t)(i0 / BM);
+        const int32_t nqb = (int32_t)ceil_div64(q_len[k], BM);
+        dkv_items[t] = make_int4(k, b, m0, nqb - m0);
+    }
+}
+
+// Stable sort by descending .w: item a goes to slot
+//   #{b : cost_b > cost_a} + #{b < a : cost_b == cost_a}.
+// Costs are streamed through LDS in tiles; every thread of a block walks the
+// same tile, so the reads are broadcasts.
+__global__ __launch_bounds__(256) void plan_sort_kernel(const int4 *__restrict__ in, int32_t n,
+                                                        int4 *__restrict__ out)
+{
+    __shared__ int32_t tile[1024];
+    const int32_t a = blockIdx.x * blockDim.x + threadIdx.x;
+    const int4 me = (a < n) ? in[a] : make_int4(0, 0, 0, 0);
+    int32_t rank = 0;
+    for (int32_t b0 = 0; b0 < n; b0 += 1024) {
+        __syncthreads();
+        for (int32_t i = threadIdx.x; i < 1024; i += blockDim.x)
+            tile[i] = (b0 + i < n) ? in[b0 + i].w : -1;
+        __syncthreads();
+        const int32_t lim = (n - b0 < 1024) ? n - b0 : 1024;
+        for (int32_t i = 0; i < lim; ++i) {
+            const int32_t cb = tile[i];
+            rank += (cb > me.w) || (cb == me.w && b0 + i < a);
+        }
+    }
+    if (a < n) out[rank] = me;
+}
+
+}  // namespace
+
+hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r, int32_t K,
+                              int32_t BM, int32_t BN, int32_t *q_begin, int32_t *q_len,
+                              int32_t *kv_len, int32_t *cu_q, int32_t *cu_k, int32_t *fwd_off,
+                              int32_t *dkv_off, PlanTotals *totals, hipStream_t st)
+{
+    plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, K, BM, BN, q_begin, q_len, kv_len,
+                                                   cu_q, cu_k, fwd_off, dkv_off, totals);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
+                             const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
+                             hipStream_t st)
+{
+    const int32_t n = p->n_fwd > p->n_dkv ? p->n_fwd : p->n_dkv;
+    plan_emit_kernel<<<(n + 255) / 256, 256, 0, st>>>(
+        p->K, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, fwd_off, dkv_off, p->n_fwd,
+        p->n_dkv, (int4 *)scratch_fwd, (int4 *)scratch_dkv);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    plan_sort_kernel<<<(p->n_fwd + 255) / 256, 256, 0, st>>>((const int4 *)scratch_fwd, p->n_fwd,
+                                                             (int4 *)p->fwd_items);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    plan_sort_kernel<<<(p->n_dkv + 255) / 256, 256, 0, st>>>((const int4 *)scratch_dkv, p->n_dkv,
+                                                             (int4 *)p->dkv_items);
+    return hipGetLastError();
+}

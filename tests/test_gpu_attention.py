@@ -1,0 +1,272 @@
+"""Parity of the HIP forward/backward with the fp64 oracle, through the C ABI.
+
+Tolerances are the stated ones: max-abs 2e-2 on O (and LSE), 5e-2 on dQ/dK/dV,
+GPU bf16 outputs widened and compared with the unrounded fp64 oracle on the
+same seeded bf16 inputs.  Small cases are compared exhaustively; the full-size
+benchmark micro-batches on seeded samples of rows / columns that the oracle
+computes one by one, plus properties that hold at any size."""
+import numpy as np
+import pytest
+
+from paper_2505_19609_amd import workloads as W
+from gpu_util import run_library, widen, bf16_ulp
+
+pytestmark = pytest.mark.gpu
+
+TOL_O, TOL_G = 2e-2, 5e-2
+
+
+def _report(name, got, ref, tol):
+    err = np.abs(got.astype(np.float64) - ref)
+    if err.size == 0:
+        return 0.0
+    i = np.unravel_index(np.argmax(err), err.shape)
+    ulps = err[i] / bf16_ulp(ref[i])
+    msg = (f"{name}: max-abs {err[i]:.4g} at {i} (ref {ref[i]:.6g}, got {got[i]:.6g}, "
+           f"{ulps:.2f} bf16 ulp), tol {tol}")
+    print(msg)
+    assert np.isfinite(got).all(), f"{name}: non-finite output"
+    assert err[i] <= tol, msg
+    return float(err[i])
+
+
+def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G):
+    out = run_library(w, block_m, block_n)
+    f = widen(out["vals"])
+    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
+    O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
+    dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
+    _report("O", out["o"], O, TOL_O)
+    _report("LSE", out["lse"], LSE, TOL_O)
+    _report("dQ", out["dq"], dQ, tol_dq)
+    _report("dK", out["dk"], dK, TOL_G)
+    _report("dV", out["dv"], dV, TOL_G)
+    out["plan"].destroy()
+
+
+def test_config1_tiny_literal(oracle):
+    """Config 1 as stated: Q pre-scaled by 1/8 in the data, no further scale.
+    dQ is then the gradient w.r.t. the pre-scaled Q, 8x the gradient w.r.t. the
+    N(0,1) draw; bf16 rounding of the exact result alone errs by 0.060 there
+    (test_config1_dq_rounding_floor), so dQ is held to 5e-2 on the latter."""
+    w = W.config(1)
+    _exhaustive(oracle, w, tol_dq=TOL_G / w.q_prescale)
+
+
+def test_config1_tiny_scale_in_kernel(oracle):
+    """Same lengths and draws, the 1/sqrt(64) applied as softmax_scale inside
+    the kernels instead: every stated tolerance applies as is."""
+    w = W.config(1)
+    w.q_prescale, w.softmax_scale = 1.0, 0.125
+    _exhaustive(oracle, w)
+
+
+def test_config2_qwen05b(oracle):
+    _exhaustive(oracle, W.config(2))
+
+
+EDGE = {
+    "single_tokens": ([1, 1, 2], [1, 1, 1], [0, 0, 0]),
+    "around_32": ([31, 32, 33], [1] * 3, [0] * 3),
+    "around_64": ([63, 64, 65], [1] * 3, [0] * 3),
+    "around_128": ([127, 128, 129, 130], [1] * 4, [0] * 4),
+    "around_256": ([255, 257], [1] * 2, [0] * 2),
+    "ragged_shards": ([1000, 999, 130, 70], [3, 7, 2, 70], [1, 6, 1, 69]),
+    "first_shards": ([900, 333], [4, 2], [0, 0]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE))
+@pytest.mark.parametrize("heads,d", [((4, 4), 64), ((6, 2), 128), ((8, 1), 128), ((2, 1), 64)])
+def test_edge_cases(oracle, name, heads, d):
+    S, N, R = EDGE[name]
+    w = W.Workload(name, S, N, R, heads[0], heads[1], d, d ** -0.5, 500 + len(S) + d)
+    _exhaustive(oracle, w)
+
+
+@pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (256, 256), (128, 64)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_block_sizes(oracle, bm, bn, d):
+    w = W.Workload("blocks", [700, 129, 1030, 64], [1, 1, 2, 1], [0, 0, 1, 0], 4, 2, d, d ** -0.5, 77)
+    _exhaustive(oracle, w, bm, bn)
+
+
+@pytest.mark.parametrize("index", [0, 7])
+def test_scaled_down_shard_twin(oracle, index):
+    """Structure of config 4 (one sequence sharded 8 ways + short local ones) at a
+    size the oracle covers exhaustively; every tile class occurs (interior,
+    diagonal, shard-offset diagonal, ragged tail)."""
+    _exhaustive(oracle, W.scaled_shard_twin(seq_len=8192, degree=8, index=index))
+
+
+def test_determinism_and_plan_reuse(oracle):
+    """No atomics anywhere: two runs are bit-identical; a plan serves many calls."""
+    import torch
+    from paper_2505_19609_amd import binding as B
+    w = W.config(2)
+    a = run_library(w, keep_device=True)
+    dev, res, plan = a["dev_in"], a["dev"], a["plan"]
+    o2, lse2 = torch.empty_like(res["o"]), torch.empty_like(res["lse"])
+    dq2, dk2, dv2 = torch.empty_like(res["dq"]), torch.empty_like(res["dk"]), torch.empty_like(res["dv"])
+    ws = torch.empty(int(plan.bwd_workspace_bytes), dtype=torch.uint8, device="cuda")
+    B.skrull_attn_fwd(plan, dev["q"], dev["k"], dev["v"], o2, lse2)
+    B.skrull_attn_bwd(plan, dev["q"], dev["k"], dev["v"], o2, lse2, dev["do"], dq2, dk2, dv2, ws)
+    torch.cuda.synchronize()
+    for x, y in ((res["o"], o2), (res["lse"], lse2), (res["dq"], dq2), (res["dk"], dk2), (res["dv"], dv2)):
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                           y.view(torch.int16) if y.dtype == torch.bfloat16 else y)
+    plan.destroy()
+
+
+def test_sequence_order_permutes_outputs(oracle):
+    """The library is agnostic to the order of sequences in the packed batch."""
+    S, N, R = [300, 64, 1000, 129], [1, 1, 4, 1], [0, 0, 2, 0]
+    w = W.Workload("perm", S, N, R, 4, 2, 128, 128 ** -0.5, 91)
+    a = run_library(w)
+    desc = oracle.ranges(S, N, R)
+    perm = [2, 0, 3, 1]
+    w2 = W.Workload("perm2", [S[i] for i in perm], [N[i] for i in perm], [R[i] for i in perm],
+                    4, 2, 128, 128 ** -0.5, 91)
+    desc2 = oracle.ranges(w2.seq_len, w2.shard_degree, w2.shard_index)
+    vals2 = {}
+    for n, cu, cu2 in (("q", "cu_q", "cu_q"), ("do", "cu_q", "cu_q"), ("k", "cu_k", "cu_k"), ("v", "cu_k", "cu_k")):
+        parts = [a["vals"][n][desc[cu][i]:desc[cu][i + 1]] for i in perm]
+        vals2[n] = np.concatenate(parts)
+    b = run_library(w2, vals=vals2)
+    for n, cu in (("o", "cu_q"), ("dq", "cu_q"), ("dk", "cu_k"), ("dv", "cu_k")):
+        for pos, i in enumerate(perm):
+            x = a[n][desc[cu][i]:desc[cu][i + 1]]
+            y = b[n][desc2[cu][pos]:desc2[cu][pos + 1]]
+            assert np.array_equal(x, y), (n, i)
+
+
+# ---------------------------------------------------------------------------
+# full-size micro-batches: sampled oracle parity + size-independent properties
+# ---------------------------------------------------------------------------
+def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400):
+    out = run_library(w)
+    f = widen(out["vals"])
+    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
+    Hq, Hkv, d = w.num_q_heads, w.num_kv_heads, w.head_dim
+    g = Hq // Hkv
+    rng = np.random.Generator(np.random.PCG64(seed))
+    # --- rows: O, LSE, dQ ---
+    es, eh, ei = [], [], []
+    for k in range(desc["num_seqs"]):
+        ql = int(desc["q_len"][k])
+        if ql <= exhaustive_below:
+            rows = np.arange(ql)
+        else:
+            fixed = [0, 1, 31, 32, 63, 64, 127, 128, ql - 129, ql - 128, ql - 65, ql - 2, ql - 1]
+            rows = np.unique(np.concatenate([np.array(fixed), rng.integers(0, ql, rows_per_long)]))
+        for i in rows:
+            heads = np.arange(Hq) if ql <= exhaustive_below else np.arange(Hq)
+            es.append(np.full(len(heads), k)); eh.append(heads); ei.append(np.full(len(heads), i))
+    ent = tuple(np.concatenate(x).astype(np.int32) for x in (es, eh, ei))
+    prow = desc["cu_q"][ent[0]] + ent[2]
+    o_ref, lse_ref = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, ent)
+    dq_ref, d_ref = oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale, ent)
+    print(f"{w.name}: checked {len(prow)} (row, head) entries of O/LSE/dQ")
+    _report("O", out["o"][prow, ent[1]], o_ref, TOL_O)
+    _report("LSE", out["lse"][ent[1], prow], lse_ref, TOL_O)
+    _report("dQ", out["dq"][prow, ent[1]], dq_ref, TOL_G)
+    # --- columns: dK, dV for the last `window` keys of long sequences (one KV
+    #     group each) and every key of the short ones (all groups) ---
+    Tq = desc["total_q"]
+    LSEf = np.full((Hq, Tq), np.nan)
+    Df = np.full((Hq, Tq), np.nan)
+    cs, cc, cj = [], [], []
+    rs, rh, ri = [], [], []
+    for k in range(desc["num_seqs"]):
+        ql, kvl, qb = int(desc["q_len"][k]), int(desc["kv_len"][k]), int(desc["q_begin"][k])
+        if ql <= exhaustive_below:
+            groups, j0 = range(Hkv), 0 if qb == 0 else kvl - ql
+        else:
+            groups, j0 = [int(rng.integers(0, Hkv))], kvl - window
+        cols = np.arange(max(j0, 0), kvl)
+        i_min = max(0, int(cols[0]) - qb)
+        for c in groups:
+            cs.append(np.full(len(cols), k)); cc.append(np.full(len(cols), c)); cj.append(cols)
+            for hh in range(c * g, (c + 1) * g):
+                ii = np.arange(i_min, ql)
+                rs.append(np.full(len(ii), k)); rh.append(np.full(len(ii), hh)); ri.append(ii)
+    need = tuple(np.concatenate(x).astype(np.int32) for x in (rs, rh, ri))
+    nrow = desc["cu_q"][need[0]] + need[2]
+    _, l_need = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, need)
+    _, d_need = oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale, need)
+    LSEf[need[1], nrow] = l_need
+    Df[need[1], nrow] = d_need
+    cent = tuple(np.concatenate(x).astype(np.int32) for x in (cs, cc, cj))
+    crow = desc["cu_k"][cent[0]] + cent[2]
+    dk_ref, dv_ref = oracle.bwd_dkv_cols(f["q"], f["k"], f["v"], f["do"], LSEf, Df, desc,
+                                         w.softmax_scale, cent)
+    assert np.isfinite(dk_ref).all() and np.isfinite(dv_ref).all()
+    print(f"{w.name}: checked {len(crow)} (key, kv head) entries of dK/dV")
+    _report("dK", out["dk"][crow, cent[1]], dk_ref, TOL_G)
+    _report("dV", out["dv"][crow, cent[1]], dv_ref, TOL_G)
+    # --- properties that hold at any size, on ALL outputs ---
+    for n in ("o", "lse", "dq", "dk", "dv"):
+        assert np.isfinite(out[n]).all(), n
+    q64, k64, v64 = (f[n].astype(np.float64) for n in ("q", "k", "v"))
+    for k in range(desc["num_seqs"]):
+        qs, qe = desc["cu_q"][k], desc["cu_q"][k + 1]
+        ks, ke = desc["cu_k"][k], desc["cu_k"][k + 1]
+        for c in range(Hkv):
+            hs = slice(c * g, (c + 1) * g)
+            tq = out["dq"][qs:qe, hs].astype(np.float64) * q64[qs:qe, hs]
+            tk = out["dk"][ks:ke, c].astype(np.float64) * k64[ks:ke, c]
+            # scale invariance of q.k: sum_i dQ_i.Q_i == sum_j dK_j.K_j per (sequence, group)
+            noise = 2.0 ** -8 * np.sqrt((tq ** 2).sum() + (tk ** 2).sum())
+            assert abs(tq.sum() - tk.sum()) <= 8 * noise + 1e-3, (k, c, tq.sum(), tk.sum(), noise)
+            # O = P V  =>  sum_j dV_j.V_j == sum_i dO_i.O_i
+            tv = out["dv"][ks:ke, c].astype(np.float64) * v64[ks:ke, c]
+            to = out["o"][qs:qe, hs].astype(np.float64) * f["do"][qs:qe, hs].astype(np.float64)
+            noise = 2.0 ** -8 * np.sqrt((tv ** 2).sum() + (to ** 2).sum())
+            assert abs(tv.sum() - to.sum()) <= 8 * noise + 1e-3, (k, c, tv.sum(), to.sum(), noise)
+    out["plan"].destroy()
+
+
+def test_config3_llama8b_sampled(oracle):
+    _sampled(oracle, W.config(3), rows_per_long=96, window=256, seed=303)
+
+
+def test_config4_shard7_sampled(oracle):
+    _sampled(oracle, W.config(4), rows_per_long=20, window=128, seed=404)
+
+
+def test_config4_shard0_sampled(oracle):
+    _sampled(oracle, W.config(4, shard_index=0), rows_per_long=64, window=256, seed=405)
+
+
+def test_config5_qwen7b_sampled(oracle):
+    _sampled(oracle, W.config(5), rows_per_long=24, window=128, seed=505)
+
+
+def test_shards_sum_to_unsharded_at_full_length():
+    """GPU vs GPU at config 3's long length: O/LSE/dQ rows of each shard equal
+    the unsharded rows bit for bit is not required (tiles differ), so compare
+    within a few bf16 ulp; zero-padded partial dK/dV summed over the shards
+    equal the unsharded dK/dV."""
+    S, N, Hq, Hkv, d = 24576, 3, 8, 2, 128
+    w = W.Workload("full", [S], [1], [0], Hq, Hkv, d, d ** -0.5, 606)
+    full = run_library(w)
+    dk_sum = np.zeros_like(full["dk"], dtype=np.float64)
+    dv_sum = np.zeros_like(full["dv"], dtype=np.float64)
+    L = S // N
+    for r in range(N):
+        b, e = r * L, (r + 1) * L
+        vals = {"q": full["vals"]["q"][b:e], "do": full["vals"]["do"][b:e],
+                "k": full["vals"]["k"][:e], "v": full["vals"]["v"][:e]}
+        ws_ = W.Workload("shard", [S], [N], [r], Hq, Hkv, d, d ** -0.5, 606)
+        sh = run_library(ws_, vals=vals)
+        assert np.abs(sh["o"] - full["o"][b:e]).max() <= 2 * 2.0 ** -7 * max(1.0, np.abs(full["o"]).max())
+        assert np.abs(sh["lse"] - full["lse"][:, b:e]).max() <= 1e-4
+        assert np.abs(sh["dq"] - full["dq"][b:e]).max() <= 2 * 2.0 ** -7 * max(1.0, np.abs(full["dq"]).max())
+        dk_sum[:e] += sh["dk"]
+        dv_sum[:e] += sh["dv"]
+        sh["plan"].destroy()
+    for name, s_, f_ in (("dk", dk_sum, full["dk"]), ("dv", dv_sum, full["dv"])):
+        err = np.abs(s_ - f_)
+        tol = (N + 1) * 0.5 * bf16_ulp(np.maximum(np.abs(f_), 1.0)) + 1e-2
+        assert (err <= tol).all(), (name, err.max())
+    full["plan"].destroy()
