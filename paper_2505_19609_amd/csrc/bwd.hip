@@ -78,7 +78,7 @@ constexpr int NW = 4;          // wavefronts per workgroup
 constexpr int SUB = 32 * NW;   // query (dQ) or key (dK/dV) rows per pass
 
 template <int D>
-__global__ __launch_bounds__(64 * NW) void dq_kernel(const BwdParams prm)
+__global__ __launch_bounds__(64 * NW, D == 128 ? 1 : 2) void dq_kernel(const BwdParams prm)
 {
     constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
     __shared__ __align__(16) unsigned char lds_k[KT * D * 2];   // K rows

@@ -40,7 +40,7 @@ constexpr int NW = 4;          // wavefronts per workgroup
 constexpr int SUB = 32 * NW;   // query rows per pass
 
 template <int D>
-__global__ __launch_bounds__(64 * NW) void fwd_kernel(const FwdParams prm)
+__global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 {
     constexpr int CH = D / 8;    // 16-byte chunks per K/V row
     constexpr int NT = 64 * NW;  // threads
