@@ -48,8 +48,9 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     constexpr int TT = D / 32;   // 32-row tiles of O^T
     static_assert(KT == TILE_ROWS, "staging helpers assume 64-row tiles");
 
-    __shared__ __align__(16) unsigned char lds_k[KT * D * 2];
-    __shared__ __align__(16) unsigned char lds_v[D * KT * 2];
+    constexpr int TILE_BYTES = KT * D * 2;
+    __shared__ __align__(16) unsigned char lds_k[2][TILE_BYTES];  // double-buffered
+    __shared__ __align__(16) unsigned char lds_v[2][TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
@@ -91,7 +92,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         for (int ks = 0; ks < KS; ++ks) qf[ks] = as_bf16x8(*(const uint4 *)(qp + 16 * ks));
     }
 
-    QuadStage<D, NT> kst, vst;
     const size_t kv_stride = (size_t)prm.Hkv * D;
     const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + c) * D;
     const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + c) * D;
@@ -101,17 +101,17 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     float m_run = -INFINITY, l_run = 0.0f;
     const float cs = prm.scale_log2;
 
-    kst.load(kp, kv_stride, 0, kvl - 1, tid);
-    vst.load(vp, kv_stride, 0, kvl - 1, tid);
+    __syncthreads();  // the previous pass is done with both buffers
+    tile_load_async<D, NT>(lds_k[0], kp, kv_stride, 0, kvl - 1, tid);
+    tile_load_async<D, NT>(lds_v[0], vp, kv_stride, 0, kvl - 1, tid);
+    wait_vmem();
+    __syncthreads();
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int kv0 = tile * KT;
-        __syncthreads();  // every wave is done reading the previous tile
-        kst.store_rm(lds_k, tid);
-        vst.store_tr(lds_v, tid);
-        __syncthreads();
-        if (tile + 1 < n_tiles) {  // in flight during the math below
-            kst.load(kp, kv_stride, kv0 + KT, kvl - 1, tid);
-            vst.load(vp, kv_stride, kv0 + KT, kvl - 1, tid);
+        const unsigned char *tk = lds_k[tile & 1], *tv = lds_v[tile & 1];
+        if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
+            tile_load_async<D, NT>(lds_k[(tile + 1) & 1], kp, kv_stride, kv0 + KT, kvl - 1, tid);
+            tile_load_async<D, NT>(lds_v[(tile + 1) & 1], vp, kv_stride, kv0 + KT, kvl - 1, tid);
         }
 
         if (wave_active && kv0 <= w_pmax) {
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                 for (int v = 0; v < 16; ++v) s[jt][v] = 0.0f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    s[jt] = mfma32(frag_rm<CH>(lds_k, 32 * jt + n, ks, h), qf[ks], s[jt]);
+                    s[jt] = mfma32(frag_rm<CH>(tk, 32 * jt + n, ks, h), qf[ks], s[jt]);
                 }
             }
             if (kv0 + KT - 1 > w_pmin) {  // tile touches the diagonal for this wave
@@ -161,10 +161,12 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                 const bf16x8 pb = acc_to_b(s[jt], kb);
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) {
-                    oacc[tt] = mfma32(frag_tr(lds_v, 32 * tt + n, kbg, h), pb, oacc[tt]);
+                    oacc[tt] = mfma32(frag_tr_rm<CH>(tv, tt, kbg, lane), pb, oacc[tt]);
                 }
             }
         }
+        wait_vmem();      // my share of the next tile has landed
+        __syncthreads();  // ... and everyone's; everyone is done reading this tile
     }
 
     if (wave_active) {

@@ -15,11 +15,44 @@
 
 constexpr int TILE_ROWS = 64;
 
-// Row-major tile, CH = D/8 chunks of 16 bytes per row.
+// Row-major tile, CH = D/8 chunks of 16 bytes per row.  The chunk index is
+// XOR-ed with a 3-bit function of the row chosen so that
+//   * 8 consecutive rows read at the same chunk (16-byte operand reads, 8 lanes
+//     per clock) land in 8 different 16-byte bank groups, and
+//   * 4 consecutive rows read at the same 32-byte column pair (transposing
+//     reads, 16 lanes per clock) land in 4 different 32-byte bank groups.
+__device__ __forceinline__ int row_swizzle(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
 template <int CH>
 __device__ __forceinline__ int rm_off(int row, int chunk)
 {
-    return (row * CH + (chunk ^ (row & 7))) * 16;
+    return (row * CH + (chunk ^ row_swizzle(row))) * 16;
+}
+
+// Transposing fragment read from a ROW-MAJOR tile (ds_read_b64_tr_b16): returns
+// the A operand of a product that contracts over the tile's rows.  For the
+// 32-column block tt and the 16-row block kbg, lane (n = lane%32, h = lane/32)
+// receives column 32*tt+n of rows 16*kbg + {4h..4h+3, 8+4h..8+4h+3}, i.e. the
+// rows its accumulator registers 8*(kbg%2)..+7 of a 32x32 result stand for.
+// The instruction works on groups of 16 lanes: lane s of a group supplies the
+// address of 4 consecutive columns of one row; lane l receives element l%4 of
+// the rows supplied by lanes l/4, l/4+4, l/4+8, l/4+12.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <int CH>
+__device__ __forceinline__ bf16x8 frag_tr_rm(const unsigned char *lds, int tt, int kbg, int lane)
+{
+    const int grp = lane >> 4, s = lane & 15, h = grp >> 1;
+    const int chunk = 4 * tt + 2 * (grp & 1) + ((s & 3) >> 1);
+    const int row = 16 * kbg + 4 * h + (s >> 2);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_ptr_t)(lds + rm_off<CH>(row, chunk) + 8 * (s & 1)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_ptr_t)(lds + rm_off<CH>(row + 8, chunk) + 8 * (s & 1)));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
 }
 
 // Transposed tile: row t = column of the source (0..D-1); 8 chunks = 64 source
@@ -31,6 +64,34 @@ __device__ __forceinline__ int tr_off(int t, int chunk)
 {
     return (t * 8 + (chunk ^ ((t ^ (t >> 3)) & 7))) * 16;
 }
+
+// Asynchronous global -> LDS copy of one 64-row x D tile in the row-major
+// swizzled layout (global_load_lds_dwordx4: no data registers, no LDS store
+// instructions).  One such instruction makes a wave write 64 consecutive
+// 16-byte LDS slots, slot = base + lane, from per-lane global addresses; the
+// swizzle is therefore applied on the global side: the lane that fills slot P
+// fetches the chunk that belongs there.  Rows beyond row_last are clamped (the
+// callers mask them).  Completion: s_waitcnt vmcnt(0) then a workgroup barrier.
+template <int D, int NT>
+__device__ __forceinline__ void tile_load_async(unsigned char *lds, const uint16_t *base,
+                                                size_t stride, int row0, int row_last, int tid)
+{
+    constexpr int CH = D / 8;
+    constexpr int PER = TILE_ROWS * CH / NT;
+    typedef void __attribute__((address_space(3))) * lds_void_t;
+    const int wave_first = tid & ~63;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+        const int P = x * NT + tid;
+        const int row = P / CH, chunk = (P % CH) ^ row_swizzle(row);
+        const uint16_t *g = base + (size_t)min(row0 + row, row_last) * stride + chunk * 8;
+        __builtin_amdgcn_global_load_lds((const void *)g, (lds_void_t)(lds + (x * NT + wave_first) * 16),
+                                         16, 0, 0);
+    }
+}
+
+// Wait until this wave's outstanding global (and global->LDS) loads have landed.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 template <int D, int NT>
 struct QuadStage {
