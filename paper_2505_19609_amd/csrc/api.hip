@@ -165,7 +165,7 @@ int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_
     info->attended_pairs = plan->pairs;
     info->useful_flops_fwd = 4 * plan->pairs * plan->d * plan->Hq;
     info->useful_flops_bwd = 10 * plan->pairs * plan->d * plan->Hq;
-    info->bwd_workspace_bytes = (((int64_t)plan->Hq * plan->total_q * 4) + 255) & ~(int64_t)255;
+    info->bwd_workspace_bytes = (((int64_t)plan->Hq * plan->total_q * 8) + 255) & ~(int64_t)255;
     return SKRULL_OK;
 }
 

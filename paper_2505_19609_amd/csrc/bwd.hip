@@ -34,7 +34,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(const uint16_t *__restrict__ o,
                                                     const uint16_t *__restrict__ d_o,
-                                                    float *__restrict__ delta, int64_t n_pairs,
+                                                    const float *__restrict__ lse,
+                                                    float *__restrict__ delta,
+                                                    float *__restrict__ lse2, int64_t n_pairs,
                                                     int32_t Hq, int32_t total_q)
 {
     constexpr int CH = D / 8;
@@ -58,12 +60,14 @@ __global__ __launch_bounds__(256) void delta_kernel(const uint16_t *__restrict__
         const int64_t row = pair / Hq;
         const int32_t hh = (int32_t)(pair % Hq);
         delta[(int64_t)hh * total_q + row] = acc;
+        // LSE in the exp2 domain, so the main kernels need no extra multiply
+        lse2[(int64_t)hh * total_q + row] = lse[(int64_t)hh * total_q + row] * kLog2e;
     }
 }
 
 struct BwdParams {
     const uint16_t *q, *k, *v, *d_o;
-    const float *lse, *delta;
+    const float *lse, *delta, *lse2;
     uint16_t *dq, *dk, *dv;
     const int4 *fwd_items, *dkv_items;
     const int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len;
@@ -78,14 +82,16 @@ constexpr int NW = 4;          // wavefronts per workgroup
 constexpr int SUB = 32 * NW;   // query (dQ) or key (dK/dV) rows per pass
 
 template <int D>
-__global__ __launch_bounds__(64 * NW, D == 128 ? 1 : 2) void dq_kernel(const BwdParams prm)
+__global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 {
     constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
-    __shared__ __align__(16) unsigned char lds_k[KT * D * 2];   // K rows
-    __shared__ __align__(16) unsigned char lds_v[KT * D * 2];   // V rows
-    __shared__ __align__(16) unsigned char lds_kt[D * KT * 2];  // K transposed
+    constexpr int TILE_BYTES = KT * D * 2;
+    // [buffer][K rows | V rows]; one array so that the V operand address is the
+    // K operand address plus a constant
+    __shared__ __align__(16) unsigned char lds_kv[2][2][TILE_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int n = lane & 31, h = lane >> 5;
     const int item_id = blockIdx.x / prm.Hq, hl = blockIdx.x % prm.Hq;
     const int g = prm.Hq / prm.Hkv;
@@ -122,10 +128,9 @@ __global__ __launch_bounds__(64 * NW, D == 128 ? 1 : 2) void dq_kernel(const Bwd
             dof[ks] = as_bf16x8(*(const uint4 *)(prm.d_o + off + 16 * ks));
         }
     }
-    const float lse2 = prm.lse[(size_t)head * prm.total_q + my_row] * kLog2e;
+    const float lse2 = prm.lse2[(size_t)head * prm.total_q + my_row];
     const float dlt = prm.delta[(size_t)head * prm.total_q + my_row];
 
-    QuadStage<D, NT> kst, vst;
     const size_t kv_stride = (size_t)prm.Hkv * D;
     const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + c) * D;
     const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + c) * D;
@@ -134,47 +139,47 @@ __global__ __launch_bounds__(64 * NW, D == 128 ? 1 : 2) void dq_kernel(const Bwd
     zero_acc(acc);
     const float cs = prm.scale_log2;
 
-    kst.load(kp, kv_stride, 0, kvl - 1, tid);
-    vst.load(vp, kv_stride, 0, kvl - 1, tid);
+    __syncthreads();  // the previous pass is done with both buffers
+    tile_load_async<D, NT>(lds_kv[0][0], kp, kv_stride, 0, kvl - 1, tid);
+    tile_load_async<D, NT>(lds_kv[0][1], vp, kv_stride, 0, kvl - 1, tid);
+    wait_vmem();
+    __syncthreads();
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int kv0 = tile * KT;
-        __syncthreads();
-        kst.store_rm(lds_k, tid);
-        kst.store_tr(lds_kt, tid);
-        vst.store_rm(lds_v, tid);
-        __syncthreads();
-        if (tile + 1 < n_tiles) {
-            kst.load(kp, kv_stride, kv0 + KT, kvl - 1, tid);
-            vst.load(vp, kv_stride, kv0 + KT, kvl - 1, tid);
+        const unsigned char *tk = lds_kv[tile & 1][0];
+        if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
+            tile_load_async<D, NT>(lds_kv[(tile + 1) & 1][0], kp, kv_stride, kv0 + KT, kvl - 1, tid);
+            tile_load_async<D, NT>(lds_kv[(tile + 1) & 1][1], vp, kv_stride, kv0 + KT, kvl - 1, tid);
         }
         if (wave_active && kv0 <= w_pmax) {
-            f32x16 s[2], dp[2];
-            zero_acc(s);
-            zero_acc(dp);
+            const bool diag = kv0 + KT - 1 > w_pmin;
+#pragma unroll 1
+            for (int jt = 0; jt < 2; ++jt) {  // 32 keys at a time keeps S^T / dP^T in 32 registers
+                f32x16 s, dp;
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
+                for (int v = 0; v < 16; ++v) { s[v] = 0.0f; dp[v] = 0.0f; }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    s[jt] = mfma32(frag_rm<CH>(lds_k, 32 * jt + n, ks, h), qf[ks], s[jt]);
-                    dp[jt] = mfma32(frag_rm<CH>(lds_v, 32 * jt + n, ks, h), dof[ks], dp[jt]);
+                    s = mfma32(frag_rm<CH>(tk, 32 * jt + n, ks, h), qf[ks], s);
+                    dp = mfma32(frag_rm<CH>(tk + TILE_BYTES, 32 * jt + n, ks, h), dof[ks], dp);
                 }
-            const bool diag = kv0 + KT - 1 > w_pmin;
-#pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float p = fast_exp2(__builtin_fmaf(s[jt][v], cs, -lse2));
+                    float p = fast_exp2(__builtin_fmaf(s[v], cs, -lse2));
                     if (diag && kv0 + 32 * jt + acc_row(v, h) > my_pos) p = 0.0f;
-                    s[jt][v] = p * (dp[jt][v] - dlt);  // dS^T
+                    s[v] = p * (dp[v] - dlt);  // dS^T
                 }
 #pragma unroll
-            for (int kbg = 0; kbg < 4; ++kbg) {
-                const bf16x8 ds = acc_to_b(s[kbg >> 1], kbg & 1);
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 ds = acc_to_b(s, kb);
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[tt] = mfma32(frag_tr(lds_kt, 32 * tt + n, kbg, h), ds, acc[tt]);
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc[tt] = mfma32(frag_tr_rm<CH>(tk, tt, 2 * jt + kb, lane), ds, acc[tt]);
+                }
             }
         }
+        wait_vmem();      // my share of the next tile has landed
+        __syncthreads();  // ... and everyone's; everyone is done reading this tile
     }
     if (wave_active && my_i < rows)
         store_rows_bf16<TT>(prm.dq + ((size_t)(qrow0 + my_i) * prm.Hq + head) * D, acc, prm.scale, h);
@@ -188,14 +193,14 @@ template <int D>
 __global__ __launch_bounds__(64 * NW) void dkv_kernel(const BwdParams prm)
 {
     constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, QT = TILE_ROWS;
-    __shared__ __align__(16) unsigned char lds_q[QT * D * 2];    // Q rows
-    __shared__ __align__(16) unsigned char lds_do[QT * D * 2];   // dO rows
-    __shared__ __align__(16) unsigned char lds_qt[D * QT * 2];   // Q transposed
-    __shared__ __align__(16) unsigned char lds_dot[D * QT * 2];  // dO transposed
-    __shared__ __align__(16) float lds_lse[QT];
-    __shared__ __align__(16) float lds_dlt[QT];
+    constexpr int TILE_BYTES = QT * D * 2;
+    // [buffer][Q rows | dO rows], row-major; the transposed operands are read
+    // from the same tiles with transposing LDS reads.
+    __shared__ __align__(16) unsigned char lds_t[2][2][TILE_BYTES];
+    __shared__ __align__(16) float lds_ld[2][2][QT];  // [buffer][LSE*log2e | D][row]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int n = lane & 31, h = lane >> 5;
     const int item_id = blockIdx.x / prm.Hkv, c = blockIdx.x % prm.Hkv;
     const int g = prm.Hq / prm.Hkv;
@@ -205,6 +210,8 @@ __global__ __launch_bounds__(64 * NW) void dkv_kernel(const BwdParams prm)
     const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
     const int kbase = prm.cu_k[seq], qbase = prm.cu_q[seq];
     const int item_rows = min(prm.BN, kvl - it.y * prm.BN);
+    const float cs = prm.scale_log2;
+    const size_t q_stride = (size_t)prm.Hq * D;
 
     for (int sub = 0; sub * SUB < item_rows; ++sub) {
     const int kv0 = it.y * prm.BN + sub * SUB;     // first key position of the pass
@@ -215,7 +222,7 @@ __global__ __launch_bounds__(64 * NW) void dkv_kernel(const BwdParams prm)
     const int my_j = wj0 + n;                      // this lane's key position
     const int my_krow = kbase + min(my_j, kvl - 1);
 
-    // K and V fragments of this lane's key row (B operands), kept for the whole kernel.
+    // K and V fragments of this lane's key row (B operands), kept for the whole pass.
     bf16x8 kf[KS], vf[KS];
     {
         const size_t off = ((size_t)my_krow * prm.Hkv + c) * D + 8 * h;
@@ -234,80 +241,114 @@ __global__ __launch_bounds__(64 * NW) void dkv_kernel(const BwdParams prm)
     f32x16 dk[TT], dv[TT];
     zero_acc(dk);
     zero_acc(dv);
-    const float cs = prm.scale_log2;
-    const size_t q_stride = (size_t)prm.Hq * D;
 
-    QuadStage<D, NT> qst, dst;
-    float lse_st = 0.0f, dlt_st = 0.0f;  // staged by threads tid < QT
-
-    auto fetch = [&](int iter) __attribute__((always_inline)) {
+    // Asynchronous fetch of (head, query tile) number `iter` into buffer `buf`:
+    // the Q and dO tiles by all waves, the 64 LSE and 64 D values by waves 0 and 1.
+    auto fetch = [&](int iter, int buf) __attribute__((always_inline)) {
         const int head = c * g + iter / n_qt;
         const int i0 = i_first + (iter % n_qt) * QT;
-        const uint16_t *qp = prm.q + ((size_t)qbase * prm.Hq + head) * D;
-        const uint16_t *dp = prm.d_o + ((size_t)qbase * prm.Hq + head) * D;
-        qst.load(qp, q_stride, i0, ql - 1, tid);
-        dst.load(dp, q_stride, i0, ql - 1, tid);
-        if (tid < QT) {
-            const int i = i0 + tid;
-            const size_t idx = (size_t)head * prm.total_q + qbase + min(i, ql - 1);
-            // rows past the end get LSE = +inf, which makes P (and dS) exactly zero
-            lse_st = (i < ql) ? prm.lse[idx] * kLog2e : INFINITY;
-            dlt_st = (i < ql) ? prm.delta[idx] : 0.0f;
+        const size_t hoff = ((size_t)qbase * prm.Hq + head) * D;
+        tile_load_async<D, NT>(lds_t[buf][0], prm.q + hoff, q_stride, i0, ql - 1, tid);
+        tile_load_async<D, NT>(lds_t[buf][1], prm.d_o + hoff, q_stride, i0, ql - 1, tid);
+        if (wave < 2) {
+            typedef void __attribute__((address_space(3))) * lds_void_t;
+            const float *src = (wave == 0 ? prm.lse2 : prm.delta) + (size_t)head * prm.total_q +
+                               qbase + min(i0 + lane, ql - 1);
+            __builtin_amdgcn_global_load_lds((const void *)src, (lds_void_t)lds_ld[buf][wave], 4, 0, 0);
         }
     };
 
-    if (n_iter > 0) fetch(0);
+    __syncthreads();  // the previous pass is done with both buffers
+    fetch(0, 0);
+    wait_vmem();
+    __syncthreads();
     for (int iter = 0; iter < n_iter; ++iter) {
         const int i0 = i_first + (iter % n_qt) * QT;
-        __syncthreads();
-        qst.store_rm(lds_q, tid);
-        qst.store_tr(lds_qt, tid);
-        dst.store_rm(lds_do, tid);
-        dst.store_tr(lds_dot, tid);
-        if (tid < QT) { lds_lse[tid] = lse_st; lds_dlt[tid] = dlt_st; }
-        __syncthreads();
-        if (iter + 1 < n_iter) fetch(iter + 1);
+        const int buf = iter & 1;
+        if (iter + 1 < n_iter) fetch(iter + 1, buf ^ 1);  // lands during the math below
+        const unsigned char *tq = lds_t[buf][0];
+        const unsigned char *tdo = lds_t[buf][1];
+        const float *t_lse = lds_ld[buf][0], *t_dlt = lds_ld[buf][1];
 
         // skip tiles whose last query still precedes this wave's first key
         if (wave_active && qb + i0 + QT - 1 >= wj0) {
-            const bool diag = qb + i0 < wj0 + 31;  // some (query, key) pair of the tile is masked
-#pragma unroll 1
-            for (int itile = 0; itile < 2; ++itile) {
-                f32x16 s, dp;
+            // masked pairs exist if a key of this wave is past a query of the tile
+            // (causal) or the tile runs past the last query row (ragged tail)
+            const bool need_mask = (qb + i0 < wj0 + 31) || (i0 + QT > ql);
+            // Fragments are fetched from LDS one phase ahead of the MFMAs that
+            // consume them; the softmax of one 32-row half runs while the matrix
+            // pipe works on the S/dP products of the other half.
+            f32x16 s[2], dp[2];
+            zero_acc(s);
+            zero_acc(dp);
+            bf16x8 fq[KS], fo[KS];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) { s[v] = 0.0f; dp[v] = 0.0f; }
+            for (int ks = 0; ks < KS; ++ks) {
+                fq[ks] = frag_rm<CH>(tq, n, ks, h);
+                fo[ks] = frag_rm<CH>(tdo, n, ks, h);
+            }
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s = mfma32(frag_rm<CH>(lds_q, 32 * itile + n, ks, h), kf[ks], s);
-                    dp = mfma32(frag_rm<CH>(lds_do, 32 * itile + n, ks, h), vf[ks], dp);
+            for (int ks = 0; ks < KS; ++ks) {
+                s[0] = mfma32(fq[ks], kf[ks], s[0]);
+                dp[0] = mfma32(fo[ks], vf[ks], dp[0]);
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                fq[ks] = frag_rm<CH>(tq, 32 + n, ks, h);
+                fo[ks] = frag_rm<CH>(tdo, 32 + n, ks, h);
+            }
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                if (half == 0) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        s[1] = mfma32(fq[ks], kf[ks], s[1]);
+                        dp[1] = mfma32(fo[ks], vf[ks], dp[1]);
+                    }
                 }
+                bf16x8 ft[TT], fu[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    ft[tt] = frag_tr_rm<CH>(tdo, tt, 2 * half, lane);
+                    fu[tt] = frag_tr_rm<CH>(tq, tt, 2 * half, lane);
+                }
+                // softmax of this half: P = exp2(S*c - LSE*log2e), dS = P (dP - D)
 #pragma unroll
                 for (int vb = 0; vb < 4; ++vb) {
-                    const int ib = 32 * itile + 8 * vb + 4 * h;  // 4 consecutive query rows
-                    const float4 l4 = *(const float4 *)(lds_lse + ib);
-                    const float4 d4 = *(const float4 *)(lds_dlt + ib);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+                    const int ib = 32 * half + 8 * vb + 4 * h;  // 4 consecutive query rows
+                    const float4 l4 = *(const float4 *)(t_lse + ib);
+                    const float4 d4 = *(const float4 *)(t_dlt + ib);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int v = 4 * vb + e;
-                        float p = fast_exp2(__builtin_fmaf(s[v], cs, -lv[e]));
-                        if (diag && my_j > qb + i0 + ib + e) p = 0.0f;
-                        s[v] = p;                        // P
-                        dp[v] = p * (dp[v] - dvv[e]);    // dS
+                        float p = fast_exp2(__builtin_fmaf(s[half][v], cs, -lv[e]));
+                        if (need_mask && (my_j > qb + i0 + ib + e || i0 + ib + e >= ql)) p = 0.0f;
+                        s[half][v] = p;
+                        dp[half][v] = p * (dp[half][v] - dd[e]);
                     }
                 }
+                const bf16x8 pb0 = acc_to_b(s[half], 0), db0 = acc_to_b(dp[half], 0);
+                const bf16x8 pb1 = acc_to_b(s[half], 1), db1 = acc_to_b(dp[half], 1);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 pb = acc_to_b(s, kb), dsb = acc_to_b(dp, kb);
-                    const int kbg = 2 * itile + kb;
+                for (int tt = 0; tt < TT; ++tt) {
+                    dv[tt] = mfma32(ft[tt], pb0, dv[tt]);
+                    dk[tt] = mfma32(fu[tt], db0, dk[tt]);
+                }
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) {
-                        dv[tt] = mfma32(frag_tr(lds_dot, 32 * tt + n, kbg, h), pb, dv[tt]);
-                        dk[tt] = mfma32(frag_tr(lds_qt, 32 * tt + n, kbg, h), dsb, dk[tt]);
-                    }
+                for (int tt = 0; tt < TT; ++tt) {
+                    ft[tt] = frag_tr_rm<CH>(tdo, tt, 2 * half + 1, lane);
+                    fu[tt] = frag_tr_rm<CH>(tq, tt, 2 * half + 1, lane);
+                }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    dv[tt] = mfma32(ft[tt], pb1, dv[tt]);
+                    dk[tt] = mfma32(fu[tt], db1, dk[tt]);
                 }
             }
         }
+        wait_vmem();      // my share of the next tile has landed
+        __syncthreads();  // ... and everyone's; everyone is done reading this tile
     }
     if (wave_active && my_j < kvl) {
         const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
@@ -325,7 +366,7 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const voi
     const int64_t n_pairs = (int64_t)p->total_q * p->Hq;
     const int64_t threads = n_pairs * (D / 8);
     delta_kernel<D><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(
-        (const uint16_t *)o, prm.d_o, delta, n_pairs, p->Hq, p->total_q);
+        (const uint16_t *)o, prm.d_o, prm.lse, delta, (float *)prm.lse2, n_pairs, p->Hq, p->total_q);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
@@ -348,6 +389,7 @@ hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     BwdParams prm;
     prm.q = (const uint16_t *)q; prm.k = (const uint16_t *)k; prm.v = (const uint16_t *)v;
     prm.d_o = (const uint16_t *)d_o; prm.lse = lse; prm.delta = delta;
+    prm.lse2 = delta + (size_t)p->Hq * p->total_q;
     prm.dq = (uint16_t *)dq; prm.dk = (uint16_t *)dk; prm.dv = (uint16_t *)dv;
     prm.fwd_items = (const int4 *)p->fwd_items; prm.dkv_items = (const int4 *)p->dkv_items;
     prm.cu_q = p->cu_q; prm.cu_k = p->cu_k; prm.q_begin = p->q_begin; prm.q_len = p->q_len;

@@ -52,7 +52,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     __shared__ __align__(16) unsigned char lds_k[2][TILE_BYTES];  // double-buffered
     __shared__ __align__(16) unsigned char lds_v[2][TILE_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int n = lane & 31, h = lane >> 5;
 
     // blockIdx -> (item, head).  Consecutive blocks go to consecutive XCDs; the
