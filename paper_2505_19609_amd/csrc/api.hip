@@ -107,7 +107,9 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     HIP_TRY(hipMemcpyAsync(tmp, p->seq_len, (size_t)K * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(tmp + kpad, p->shard_degree, (size_t)K * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(tmp + 2 * kpad, p->shard_index, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(launch_plan_ranges(tmp, tmp + kpad, tmp + 2 * kpad, K, BM, BN, plan->q_begin,
+    HIP_TRY(launch_plan_ranges(tmp, tmp + kpad, tmp + 2 * kpad, K, BM, BN,
+                               INT32_MAX / (p->num_q_heads * p->head_dim),
+                               INT32_MAX / (p->num_kv_heads * p->head_dim), plan->q_begin,
                                plan->q_len, plan->kv_len, plan->cu_q, plan->cu_k, tmp + 3 * kpad,
                                tmp + 4 * kpad, totals_d, st));
     HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));

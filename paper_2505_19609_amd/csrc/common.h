@@ -29,7 +29,8 @@ struct PlanTotals {
 
 // plan.hip
 hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r, int32_t K,
-                              int32_t BM, int32_t BN, int32_t *q_begin, int32_t *q_len,
+                              int32_t BM, int32_t BN, int32_t max_q_rows, int32_t max_k_rows,
+                              int32_t *q_begin, int32_t *q_len,
                               int32_t *kv_len, int32_t *cu_q, int32_t *cu_k, int32_t *fwd_off,
                               int32_t *dkv_off, PlanTotals *totals, hipStream_t st);
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,

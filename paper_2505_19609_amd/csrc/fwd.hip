@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         for (int ks = 0; ks < KS; ++ks) qf[ks] = as_bf16x8(*(const uint4 *)(qp + 16 * ks));
     }
 
-    const size_t kv_stride = (size_t)prm.Hkv * D;
+    const uint32_t kv_stride = (uint32_t)prm.Hkv * D;
     const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + c) * D;
     const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + c) * D;
 

@@ -42,7 +42,8 @@ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) 
 
 __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
     const int32_t *__restrict__ S, const int32_t *__restrict__ N, const int32_t *__restrict__ R,
-    int32_t K, int32_t BM, int32_t BN, int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
+    int32_t K, int32_t BM, int32_t BN, int32_t max_q_rows, int32_t max_k_rows,
+    int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
     int32_t *__restrict__ kv_len, int32_t *__restrict__ cu_q, int32_t *__restrict__ cu_k,
     int32_t *__restrict__ fwd_off, int32_t *__restrict__ dkv_off, PlanTotals *__restrict__ totals)
 {
@@ -63,6 +64,9 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
                 qb = (r * s) / n;
                 kl = ((r + 1) * s) / n;
                 ql = kl - qb;
+                // one sequence of one tensor must span fewer than 2^31 elements
+                // (the kernels address inside a sequence with 32-bit offsets)
+                if (ql > max_q_rows || kl > max_k_rows) atomicMin(&first_bad, k);
                 nf = ceil_div64(ql, BM);
                 nd = ceil_div64(kl, BN);
                 pr = (kl * (kl + 1) - qb * (qb + 1)) / 2;
@@ -170,11 +174,12 @@ __global__ __launch_bounds__(256) void plan_sort_kernel(const int4 *__restrict__
 }  // namespace
 
 hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r, int32_t K,
-                              int32_t BM, int32_t BN, int32_t *q_begin, int32_t *q_len,
+                              int32_t BM, int32_t BN, int32_t max_q_rows, int32_t max_k_rows,
+                              int32_t *q_begin, int32_t *q_len,
                               int32_t *kv_len, int32_t *cu_q, int32_t *cu_k, int32_t *fwd_off,
                               int32_t *dkv_off, PlanTotals *totals, hipStream_t st)
 {
-    plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, K, BM, BN, q_begin, q_len, kv_len,
+    plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, K, BM, BN, max_q_rows, max_k_rows, q_begin, q_len, kv_len,
                                                    cu_q, cu_k, fwd_off, dkv_off, totals);
     return hipGetLastError();
 }

@@ -15,18 +15,27 @@
 
 constexpr int TILE_ROWS = 64;
 
-// Row-major tile, CH = D/8 chunks of 16 bytes per row.  The chunk index is
-// XOR-ed with a 3-bit function of the row chosen so that
-//   * 8 consecutive rows read at the same chunk (16-byte operand reads, 8 lanes
-//     per clock) land in 8 different 16-byte bank groups, and
-//   * 4 consecutive rows read at the same 32-byte column pair (transposing
-//     reads, 16 lanes per clock) land in 4 different 32-byte bank groups.
-__device__ __forceinline__ int row_swizzle(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// Row-major tile, CH = D/8 chunks of 16 bytes per row.  LDS has 64 banks of 4
+// bytes (a 256-byte line); a wave's 16-byte reads are served 16 lanes at a time
+// and its 8-byte reads 32 lanes at a time, so a group is conflict-free when its
+// 16-byte slots are distinct modulo 256 bytes.  The chunk index is XOR-ed with
+// a function of the row chosen so that
+//   * 16 consecutive rows read at the same chunk (MFMA operand reads), and
+//   * 4 consecutive rows x 4 consecutive chunks (transposing reads)
+// both touch 16 different slots.  At d=128 a row is one line, so the function
+// must take 16 values over 16 rows; at d=64 two rows share a line and 8 values
+// over 16 rows suffice.
+template <int CH>
+__device__ __forceinline__ int row_swizzle(int row)
+{
+    if (CH == 16) return ((row & 3) << 2) | ((row >> 2) & 3);
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
 
 template <int CH>
 __device__ __forceinline__ int rm_off(int row, int chunk)
 {
-    return (row * CH + (chunk ^ row_swizzle(row))) * 16;
+    return (row * CH + (chunk ^ row_swizzle<CH>(row))) * 16;
 }
 
 // Transposing fragment read from a ROW-MAJOR tile (ds_read_b64_tr_b16): returns
@@ -72,9 +81,10 @@ __device__ __forceinline__ int tr_off(int t, int chunk)
 // swizzle is therefore applied on the global side: the lane that fills slot P
 // fetches the chunk that belongs there.  Rows beyond row_last are clamped (the
 // callers mask them).  Completion: s_waitcnt vmcnt(0) then a workgroup barrier.
+// `base` must be wave-uniform (row 0 of the sequence, already offset to the head).
 template <int D, int NT>
 __device__ __forceinline__ void tile_load_async(unsigned char *lds, const uint16_t *base,
-                                                size_t stride, int row0, int row_last, int tid)
+                                                uint32_t stride, int row0, int row_last, int tid)
 {
     constexpr int CH = D / 8;
     constexpr int PER = TILE_ROWS * CH / NT;
@@ -83,8 +93,11 @@ __device__ __forceinline__ void tile_load_async(unsigned char *lds, const uint16
 #pragma unroll
     for (int x = 0; x < PER; ++x) {
         const int P = x * NT + tid;
-        const int row = P / CH, chunk = (P % CH) ^ row_swizzle(row);
-        const uint16_t *g = base + (size_t)min(row0 + row, row_last) * stride + chunk * 8;
+        const int row = P / CH, chunk = (P % CH) ^ row_swizzle<CH>(row);
+        // 32-bit element offset from a wave-uniform base (the plan guarantees that
+        // one sequence of one tensor spans fewer than 2^31 elements)
+        const uint32_t eoff = (uint32_t)min(row0 + row, row_last) * stride + (uint32_t)(chunk * 8);
+        const uint16_t *g = base + eoff;
         __builtin_amdgcn_global_load_lds((const void *)g, (lds_void_t)(lds + (x * NT + wave_first) * 16),
                                          16, 0, 0);
     }
@@ -161,6 +174,49 @@ struct QuadStage {
                 }
             }
         }
+    }
+};
+
+// Per-lane byte offsets of the MFMA operand fragments inside a row-major tile,
+// computed once per kernel.  Everything that varies inside the hot loops (which
+// 32-row block, which 16-row block, which of two adjacent tiles) is then a
+// compile-time constant added to one of these, i.e. an instruction immediate:
+//   operand rows 32*b+n, k-step ks          : rm[ks] + b * 32*ROWB
+//   transposed, column block tt, rows 16*kbg : trl[tt] / trh[tt] + kbg * 16*ROWB
+// (the swizzle only looks at the row modulo 16, so adding 16 or 32 rows keeps it).
+template <int D>
+struct FragAddr {
+    static constexpr int CH = D / 8, KS = D / 16, TT = D / 32, ROWB = D * 2;
+    int rm[KS];
+    int trl[TT], trh[TT];
+
+    __device__ __forceinline__ void init(int lane)
+    {
+        const int n = lane & 31, h = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) rm[ks] = rm_off<CH>(n, 2 * ks + h);
+        const int grp = lane >> 4, s = lane & 15;
+        const int row = 4 * (grp >> 1) + (s >> 2);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const int chunk = 4 * tt + 2 * (grp & 1) + ((s & 3) >> 1);
+            trl[tt] = rm_off<CH>(row, chunk) + 8 * (s & 1);
+            trh[tt] = rm_off<CH>(row + 8, chunk) + 8 * (s & 1);
+        }
+    }
+    // rows 32*b + n of the tile at `t`, k-step ks
+    __device__ __forceinline__ bf16x8 rows(const unsigned char *t, int b, int ks, int extra = 0) const
+    {
+        return *(const bf16x8 *)(t + rm[ks] + b * (32 * ROWB) + extra);
+    }
+    // transposed fragment: column block tt, row block kbg (see frag_tr_rm)
+    __device__ __forceinline__ bf16x8 cols(const unsigned char *t, int tt, int kbg, int extra = 0) const
+    {
+        typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(t + trl[tt] + kbg * (16 * ROWB) + extra));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(t + trh[tt] + kbg * (16 * ROWB) + extra));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, both);
     }
 };
 
