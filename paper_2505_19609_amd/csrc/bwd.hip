@@ -455,12 +455,17 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams p
         const int i0 = i_first + (T % n_qt) * QT;
         const int buf = T % 3;
         const size_t hoff = ((size_t)qbase * prm.Hq + head) * D;
-        tile_load_async<D, NT>(lds_t[buf][0], prm.q + hoff, q_stride, i0, ql - 1, tid);
-        tile_load_async<D, NT>(lds_t[buf][1], prm.d_o + hoff, q_stride, i0, ql - 1, tid);
+        // the thread index goes through an opaque copy so that the per-lane part of
+        // the addresses is recomputed here (a few VALU ops per tile) instead of
+        // being kept in registers across the whole loop
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        tile_load_async<D, NT>(lds_t[buf][0], prm.q + hoff, q_stride, i0, ql - 1, t);
+        tile_load_async<D, NT>(lds_t[buf][1], prm.d_o + hoff, q_stride, i0, ql - 1, t);
         if (wave < 2) {
             typedef void __attribute__((address_space(3))) * lds_void_t;
             const float *src = (wave == 0 ? prm.lse2 : prm.delta) + (size_t)head * prm.total_q +
-                               qbase + min(i0 + lane, ql - 1);
+                               qbase + min(i0 + (t & 63), ql - 1);
             __builtin_amdgcn_global_load_lds((const void *)src, (lds_void_t)lds_ld[buf][wave], 4, 0, 0);
         }
     };

@@ -97,6 +97,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + c) * D;
     const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + c) * D;
 
+    FragAddr<D> fa;
+    fa.init(lane);
     f32x16 oacc[TT];
     zero_acc(oacc);
     float m_run = -INFINITY, l_run = 0.0f;
@@ -117,21 +119,35 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 
         if (wave_active && kv0 <= w_pmax) {
             f32x16 s[2];
+            zero_acc(s);
+            // operand fragments are read from LDS in groups ahead of the MFMAs that use them
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt) {
+            for (int kh = 0; kh < 2; ++kh) {
+                bf16x8 f0[KS / 2], f1[KS / 2];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) s[jt][v] = 0.0f;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s[jt] = mfma32(frag_rm<CH>(tk, 32 * jt + n, ks, h), qf[ks], s[jt]);
+                for (int x = 0; x < KS / 2; ++x) {
+                    f0[x] = fa.rows(tk, 0, kh * (KS / 2) + x);
+                    f1[x] = fa.rows(tk, 1, kh * (KS / 2) + x);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int x = 0; x < KS / 2; ++x) {  // two independent accumulation chains
+                    s[0] = mfma32(f0[x], qf[kh * (KS / 2) + x], s[0]);
+                    s[1] = mfma32(f1[x], qf[kh * (KS / 2) + x], s[1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            // first transposed V fragments: their latency hides behind the softmax arithmetic
+            bf16x8 fv[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) fv[tt] = fa.cols(tv, tt, 0);
+            __builtin_amdgcn_sched_barrier(0);
             if (kv0 + KT - 1 > w_pmin) {  // tile touches the diagonal for this wave
 #pragma unroll
                 for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
-                        if (kv0 + 32 * jt + acc_row(v, h) > my_pos) s[jt][v] = -INFINITY;
+                        s[jt][v] = (kv0 + 32 * jt + acc_row(v, h) > my_pos) ? -INFINITY : s[jt][v];
             }
             float mx = s[0][0];
 #pragma unroll
@@ -140,7 +156,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                 for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[jt][v]);
             mx = fmaxf(mx, xor32(mx));
             const float m_new = fmaxf(m_run, mx * cs);
-            const float alpha = fast_exp2(m_run - m_new);
             float rs = 0.0f;
 #pragma unroll
             for (int jt = 0; jt < 2; ++jt)
@@ -150,19 +165,25 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                     s[jt][v] = p;
                     rs += p;
                 }
-            l_run = l_run * alpha + rs;
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {  // rescale only when a max moved
+                const float alpha = fast_exp2(m_run - m_new);
+                l_run *= alpha;
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[tt][v] *= alpha;
+            }
+            l_run += rs;
             m_run = m_new;
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[tt][v] *= alpha;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kbg = 0; kbg < 4; ++kbg) {
-                const int jt = kbg >> 1, kb = kbg & 1;
-                const bf16x8 pb = acc_to_b(s[jt], kb);
+                const bf16x8 pb = acc_to_b(s[kbg >> 1], kbg & 1);
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    oacc[tt] = mfma32(frag_tr_rm<CH>(tv, tt, kbg, lane), pb, oacc[tt]);
+                for (int tt = 0; tt < TT; ++tt) oacc[tt] = mfma32(fv[tt], pb, oacc[tt]);
+                if (kbg < 3) {
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) fv[tt] = fa.cols(tv, tt, kbg + 1);
                 }
             }
         }
