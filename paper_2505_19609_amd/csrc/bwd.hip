@@ -86,8 +86,8 @@ constexpr int SUB = 32 * NW;   // query (dQ) or key (dK/dV) rows per pass
 template <int D>
 __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 {
-    constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
-    constexpr int TILE_BYTES = KT * D * 2;
+    constexpr int NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
+    constexpr int TILE_BYTES = TileGeom<D>::BYTES;
     // [buffer][K rows | V rows]; one array so that the V operand address is the
     // K operand address plus a constant
     __shared__ __align__(16) unsigned char lds_kv[2][2][TILE_BYTES];
@@ -99,6 +99,11 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
     const int g = prm.Hq / prm.Hkv;
     const int c = hl % prm.Hkv;
     const int head = c * g + hl / prm.Hkv;
+
+    FragAddr<D> fa;
+    fa.init(lane);
+    TileLoader<D, NT> ld;
+    ld.init(tid, (uint32_t)prm.Hkv * D * 2);
 
     const int4 it = prm.fwd_items[item_id];
     const int seq = it.x;
@@ -132,32 +137,27 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
             dof[ks] = as_bf16x8(*(const uint4 *)(prm.d_o + off + 16 * ks));
         }
     }
-    FragAddr<D> fa;
-    fa.init(lane);
     const float lse2 = prm.lse2[(size_t)head * prm.total_q + my_row];
     const float dlt = prm.delta[(size_t)head * prm.total_q + my_row];
 
-    const uint32_t kv_stride = (uint32_t)prm.Hkv * D;
-    int cc = c;
-    asm volatile("" : "+s"(cc));  // keep the tile addresses' invariants inside the pass
-    const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + cc) * D;
-    const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + cc) * D;
+    const __amdgpu_buffer_rsrc_t rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+    const __amdgpu_buffer_rsrc_t rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
 
     f32x16 acc[TT];
     zero_acc(acc);
     const float cs = prm.scale_log2;
 
     __syncthreads();  // the previous pass is done with both buffers
-    tile_load_async<D, NT>(lds_kv[0][0], kp, kv_stride, 0, kvl - 1, tid);
-    tile_load_async<D, NT>(lds_kv[0][1], vp, kv_stride, 0, kvl - 1, tid);
+    ld.load(rk, lds_kv[0][0], 0, tid);
+    ld.load(rv, lds_kv[0][1], 0, tid);
     wait_vmem();
     __syncthreads();
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int kv0 = tile * KT;
         const unsigned char *tk = lds_kv[tile & 1][0];
         if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
-            tile_load_async<D, NT>(lds_kv[(tile + 1) & 1][0], kp, kv_stride, kv0 + KT, kvl - 1, tid);
-            tile_load_async<D, NT>(lds_kv[(tile + 1) & 1][1], vp, kv_stride, kv0 + KT, kvl - 1, tid);
+            ld.load(rk, lds_kv[(tile + 1) & 1][0], kv0 + KT, tid);
+            ld.load(rv, lds_kv[(tile + 1) & 1][1], kv0 + KT, tid);
         }
         if (wave_active && kv0 <= w_pmax) {
             const bool diag = kv0 + KT - 1 > w_pmin;  // some key of the tile is past some query
@@ -166,13 +166,14 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
             // operand reads run a few MFMAs ahead of their use.
 #pragma unroll 1
             for (int jt = 0; jt < 2; ++jt) {
+                const unsigned char *th = tk + jt * (32 * TileGeom<D>::ROWB);  // this half's 32 keys
                 f32x16 s, dp;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) { s[v] = 0.0f; dp[v] = 0.0f; }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    s = mfma32(fa.rows(tk, 0, ks, jt * 32 * D * 2), qf[ks], s);
-                    dp = mfma32(fa.rows(tk + TILE_BYTES, 0, ks, jt * 32 * D * 2), dof[ks], dp);
+                    s = mfma32(fa.rows(th, 0, ks), qf[ks], s);
+                    dp = mfma32(fa.rows(th + TILE_BYTES, 0, ks), dof[ks], dp);
                 }
                 if (diag) {
 #pragma unroll
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
                     const bf16x8 ds = acc_to_b(s, kb);
 #pragma unroll
                     for (int tt = 0; tt < TT; ++tt)
-                        acc[tt] = mfma32(fa.cols(tk, tt, kb, jt * 32 * D * 2), ds, acc[tt]);
+                        acc[tt] = mfma32(fa.cols(th, tt, kb), ds, acc[tt]);
                 }
             }
         }
@@ -209,181 +210,9 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 }
 
 // ---------------------------------------------------------------------------
-// dK / dV
-// ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(64 * NW) void dkv_kernel(const BwdParams prm)
-{
-    constexpr int CH = D / 8, NT = 64 * NW, KS = D / 16, TT = D / 32, QT = TILE_ROWS;
-    constexpr int TILE_BYTES = QT * D * 2;
-    // [buffer][Q rows | dO rows], row-major; the transposed operands are read
-    // from the same tiles with transposing LDS reads.
-    __shared__ __align__(16) unsigned char lds_t[2][2][TILE_BYTES];
-    __shared__ __align__(16) float lds_ld[2][2][QT];  // [buffer][LSE*log2e | D][row]
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
-    const int n = lane & 31, h = lane >> 5;
-    const int item_id = blockIdx.x / prm.Hkv, c = blockIdx.x % prm.Hkv;
-    const int g = prm.Hq / prm.Hkv;
-
-    const int4 it = prm.dkv_items[item_id];
-    const int seq = it.x;
-    const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
-    const int kbase = prm.cu_k[seq], qbase = prm.cu_q[seq];
-    const int item_rows = min(prm.BN, kvl - it.y * prm.BN);
-    const float cs = prm.scale_log2;
-    const uint32_t q_stride = (uint32_t)prm.Hq * D;
-
-    for (int sub = 0; sub * SUB < item_rows; ++sub) {
-    const int kv0 = it.y * prm.BN + sub * SUB;     // first key position of the pass
-    const int krows = min(SUB, kvl - kv0);
-
-    const int wj0 = kv0 + 32 * wave;               // this wave's first key position
-    const bool wave_active = 32 * wave < krows;
-    const int my_j = wj0 + n;                      // this lane's key position
-    const int my_krow = kbase + min(my_j, kvl - 1);
-
-    // K and V fragments of this lane's key row (B operands), kept for the whole pass.
-    bf16x8 kf[KS], vf[KS];
-    {
-        const size_t off = ((size_t)my_krow * prm.Hkv + c) * D + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = as_bf16x8(*(const uint4 *)(prm.k + off + 16 * ks));
-            vf[ks] = as_bf16x8(*(const uint4 *)(prm.v + off + 16 * ks));
-        }
-    }
-
-    // first local query row that can see key kv0, rounded down to a tile
-    const int i_first = (max(0, kv0 - qb) / QT) * QT;
-    const int n_qt = (ql - i_first + QT - 1) / QT;
-    const int n_iter = n_qt * g;
-
-    f32x16 dk[TT], dv[TT];
-    zero_acc(dk);
-    zero_acc(dv);
-
-    // Asynchronous fetch of (head, query tile) number `iter` into buffer `buf`:
-    // the Q and dO tiles by all waves, the 64 LSE and 64 D values by waves 0 and 1.
-    auto fetch = [&](int iter, int buf) __attribute__((always_inline)) {
-        const int head = c * g + iter / n_qt;
-        const int i0 = i_first + (iter % n_qt) * QT;
-        const size_t hoff = ((size_t)qbase * prm.Hq + head) * D;
-        tile_load_async<D, NT>(lds_t[buf][0], prm.q + hoff, q_stride, i0, ql - 1, tid);
-        tile_load_async<D, NT>(lds_t[buf][1], prm.d_o + hoff, q_stride, i0, ql - 1, tid);
-        if (wave < 2) {
-            typedef void __attribute__((address_space(3))) * lds_void_t;
-            const float *src = (wave == 0 ? prm.lse2 : prm.delta) + (size_t)head * prm.total_q +
-                               qbase + min(i0 + lane, ql - 1);
-            __builtin_amdgcn_global_load_lds((const void *)src, (lds_void_t)lds_ld[buf][wave], 4, 0, 0);
-        }
-    };
-
-    __syncthreads();  // the previous pass is done with both buffers
-    fetch(0, 0);
-    wait_vmem();
-    __syncthreads();
-    for (int iter = 0; iter < n_iter; ++iter) {
-        const int i0 = i_first + (iter % n_qt) * QT;
-        const int buf = iter & 1;
-        if (iter + 1 < n_iter) fetch(iter + 1, buf ^ 1);  // lands during the math below
-        const unsigned char *tq = lds_t[buf][0];
-        const unsigned char *tdo = lds_t[buf][1];
-        const float *t_lse = lds_ld[buf][0], *t_dlt = lds_ld[buf][1];
-
-        // skip tiles whose last query still precedes this wave's first key
-        if (wave_active && qb + i0 + QT - 1 >= wj0) {
-            // masked pairs exist if a key of this wave is past a query of the tile
-            // (causal) or the tile runs past the last query row (ragged tail)
-            const bool need_mask = (qb + i0 < wj0 + 31) || (i0 + QT > ql);
-            // Fragments are fetched from LDS one phase ahead of the MFMAs that
-            // consume them; the softmax of one 32-row half runs while the matrix
-            // pipe works on the S/dP products of the other half.
-            f32x16 s[2], dp[2];
-            zero_acc(s);
-            zero_acc(dp);
-            bf16x8 fq[KS], fo[KS];
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                fq[ks] = frag_rm<CH>(tq, n, ks, h);
-                fo[ks] = frag_rm<CH>(tdo, n, ks, h);
-            }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                s[0] = mfma32(fq[ks], kf[ks], s[0]);
-                dp[0] = mfma32(fo[ks], vf[ks], dp[0]);
-            }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                fq[ks] = frag_rm<CH>(tq, 32 + n, ks, h);
-                fo[ks] = frag_rm<CH>(tdo, 32 + n, ks, h);
-            }
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                if (half == 0) {
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        s[1] = mfma32(fq[ks], kf[ks], s[1]);
-                        dp[1] = mfma32(fo[ks], vf[ks], dp[1]);
-                    }
-                }
-                bf16x8 ft[TT], fu[TT];
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    ft[tt] = frag_tr_rm<CH>(tdo, tt, 2 * half, lane);
-                    fu[tt] = frag_tr_rm<CH>(tq, tt, 2 * half, lane);
-                }
-                // softmax of this half: P = exp2(S*c - LSE*log2e), dS = P (dP - D)
-#pragma unroll
-                for (int vb = 0; vb < 4; ++vb) {
-                    const int ib = 32 * half + 8 * vb + 4 * h;  // 4 consecutive query rows
-                    const float4 l4 = *(const float4 *)(t_lse + ib);
-                    const float4 d4 = *(const float4 *)(t_dlt + ib);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int v = 4 * vb + e;
-                        float p = fast_exp2(__builtin_fmaf(s[half][v], cs, -lv[e]));
-                        if (need_mask && (my_j > qb + i0 + ib + e || i0 + ib + e >= ql)) p = 0.0f;
-                        s[half][v] = p;
-                        dp[half][v] = p * (dp[half][v] - dd[e]);
-                    }
-                }
-                const bf16x8 pb0 = acc_to_b(s[half], 0), db0 = acc_to_b(dp[half], 0);
-                const bf16x8 pb1 = acc_to_b(s[half], 1), db1 = acc_to_b(dp[half], 1);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    dv[tt] = mfma32(ft[tt], pb0, dv[tt]);
-                    dk[tt] = mfma32(fu[tt], db0, dk[tt]);
-                }
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    ft[tt] = frag_tr_rm<CH>(tdo, tt, 2 * half + 1, lane);
-                    fu[tt] = frag_tr_rm<CH>(tq, tt, 2 * half + 1, lane);
-                }
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    dv[tt] = mfma32(ft[tt], pb1, dv[tt]);
-                    dk[tt] = mfma32(fu[tt], db1, dk[tt]);
-                }
-            }
-        }
-        wait_vmem();      // my share of the next tile has landed
-        __syncthreads();  // ... and everyone's; everyone is done reading this tile
-    }
-    if (wave_active && my_j < kvl) {
-        const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
-        store_rows_bf16<TT>(prm.dk + off, dk, prm.scale, h);
-        store_rows_bf16<TT>(prm.dv + off, dv, 1.0f, h);
-    }
-    }  // pass
-}
-
-// ---------------------------------------------------------------------------
-// dK / dV, paired-wave version.
+// dK / dV, paired waves.
 //
-// The single-wave version above needs K, V, dK and dV of its 32 key rows in
+// One wave owning 32 key rows would need K, V, dK and dV of those rows in
 // registers (192 of them at d=128), which pins it to one wave per SIMD with
 // nothing to hide LDS latency or softmax arithmetic behind.  Here two waves that
 // share a SIMD share the 32 key rows instead:
@@ -401,8 +230,8 @@ constexpr int NWP = 8;  // 4 S waves + 4 dP waves
 template <int D>
 __global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams prm)
 {
-    constexpr int CH = D / 8, NT = 64 * NWP, KS = D / 16, TT = D / 32, QT = TILE_ROWS;
-    constexpr int TILE_BYTES = QT * D * 2;
+    constexpr int NT = 64 * NWP, KS = D / 16, TT = D / 32, QT = TILE_ROWS;
+    constexpr int TILE_BYTES = TileGeom<D>::BYTES;
     __shared__ __align__(16) unsigned char lds_t[3][2][TILE_BYTES];  // [ring][Q | dO] rows
     __shared__ __align__(16) float lds_ld[3][2][QT];                 // [ring][LSE*log2e | D]
     __shared__ __align__(16) unsigned char lds_p[4][2][2][1024];     // [pair][parity][half][lane*16]
@@ -415,6 +244,8 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams p
     const int g = prm.Hq / prm.Hkv;
     FragAddr<D> fa;
     fa.init(lane);
+    TileLoader<D, NT> ld;
+    ld.init(tid, (uint32_t)prm.Hq * D * 2);
 
     const int4 it = prm.dkv_items[item_id];
     const int seq = it.x;
@@ -422,7 +253,6 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams p
     const int kbase = prm.cu_k[seq], qbase = prm.cu_q[seq];
     const int item_rows = min(prm.BN, kvl - it.y * prm.BN);
     const float cs = prm.scale_log2;
-    const uint32_t q_stride = (uint32_t)prm.Hq * D;
 
     for (int sub = 0; sub * SUB < item_rows; ++sub) {
     const int kv0 = it.y * prm.BN + sub * SUB;  // first key position of the pass
@@ -455,17 +285,13 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams p
         const int i0 = i_first + (T % n_qt) * QT;
         const int buf = T % 3;
         const size_t hoff = ((size_t)qbase * prm.Hq + head) * D;
-        // the thread index goes through an opaque copy so that the per-lane part of
-        // the addresses is recomputed here (a few VALU ops per tile) instead of
-        // being kept in registers across the whole loop
-        int t = tid;
-        asm volatile("" : "+v"(t));
-        tile_load_async<D, NT>(lds_t[buf][0], prm.q + hoff, q_stride, i0, ql - 1, t);
-        tile_load_async<D, NT>(lds_t[buf][1], prm.d_o + hoff, q_stride, i0, ql - 1, t);
+        // query rows past the end of the sequence read as zero (and are masked)
+        ld.load(ld.rsrc(prm.q + hoff, ql), lds_t[buf][0], i0, tid);
+        ld.load(ld.rsrc(prm.d_o + hoff, ql), lds_t[buf][1], i0, tid);
         if (wave < 2) {
             typedef void __attribute__((address_space(3))) * lds_void_t;
             const float *src = (wave == 0 ? prm.lse2 : prm.delta) + (size_t)head * prm.total_q +
-                               qbase + min(i0 + (t & 63), ql - 1);
+                               qbase + min(i0 + lane, ql - 1);
             __builtin_amdgcn_global_load_lds((const void *)src, (lds_void_t)lds_ld[buf][wave], 4, 0, 0);
         }
     };

@@ -42,13 +42,12 @@ constexpr int SUB = 32 * NW;   // query rows per pass
 template <int D>
 __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 {
-    constexpr int CH = D / 8;    // 16-byte chunks per K/V row
     constexpr int NT = 64 * NW;  // threads
     constexpr int KS = D / 16;   // MFMA k-steps of Q.K^T
     constexpr int TT = D / 32;   // 32-row tiles of O^T
     static_assert(KT == TILE_ROWS, "staging helpers assume 64-row tiles");
 
-    constexpr int TILE_BYTES = KT * D * 2;
+    constexpr int TILE_BYTES = TileGeom<D>::BYTES;
     __shared__ __align__(16) unsigned char lds_k[2][TILE_BYTES];  // double-buffered
     __shared__ __align__(16) unsigned char lds_v[2][TILE_BYTES];
 
@@ -63,6 +62,11 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const int g = prm.Hq / prm.Hkv;
     const int c = hl % prm.Hkv;
     const int head = c * g + hl / prm.Hkv;
+
+    FragAddr<D> fa;
+    fa.init(lane);
+    TileLoader<D, NT> ld;
+    ld.init(tid, (uint32_t)prm.Hkv * D * 2);
 
     const int4 it = prm.items[item_id];
     const int seq = it.x;
@@ -93,28 +97,25 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         for (int ks = 0; ks < KS; ++ks) qf[ks] = as_bf16x8(*(const uint4 *)(qp + 16 * ks));
     }
 
-    const uint32_t kv_stride = (uint32_t)prm.Hkv * D;
-    const uint16_t *kp = prm.k + ((size_t)kbase * prm.Hkv + c) * D;
-    const uint16_t *vp = prm.v + ((size_t)kbase * prm.Hkv + c) * D;
+    const __amdgpu_buffer_rsrc_t rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+    const __amdgpu_buffer_rsrc_t rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
 
-    FragAddr<D> fa;
-    fa.init(lane);
     f32x16 oacc[TT];
     zero_acc(oacc);
     float m_run = -INFINITY, l_run = 0.0f;
     const float cs = prm.scale_log2;
 
     __syncthreads();  // the previous pass is done with both buffers
-    tile_load_async<D, NT>(lds_k[0], kp, kv_stride, 0, kvl - 1, tid);
-    tile_load_async<D, NT>(lds_v[0], vp, kv_stride, 0, kvl - 1, tid);
+    ld.load(rk, lds_k[0], 0, tid);
+    ld.load(rv, lds_v[0], 0, tid);
     wait_vmem();
     __syncthreads();
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int kv0 = tile * KT;
         const unsigned char *tk = lds_k[tile & 1], *tv = lds_v[tile & 1];
         if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
-            tile_load_async<D, NT>(lds_k[(tile + 1) & 1], kp, kv_stride, kv0 + KT, kvl - 1, tid);
-            tile_load_async<D, NT>(lds_v[(tile + 1) & 1], vp, kv_stride, kv0 + KT, kvl - 1, tid);
+            ld.load(rk, lds_k[(tile + 1) & 1], kv0 + KT, tid);
+            ld.load(rv, lds_v[(tile + 1) & 1], kv0 + KT, tid);
         }
 
         if (wave_active && kv0 <= w_pmax) {
