@@ -14,7 +14,7 @@ SOURCES = ["api.hip", "plan.hip", "fwd.hip", "bwd.hip"]
 # packed fp32 VALU ops are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def _compile(src: str) -> str:

@@ -88,9 +88,12 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 {
     constexpr int NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
     constexpr int TILE_BYTES = TileGeom<D>::BYTES;
-    // [buffer][K rows | V rows]; one array so that the V operand address is the
-    // K operand address plus a constant
-    __shared__ __align__(16) unsigned char lds_kv[2][2][TILE_BYTES];
+    // Two [K rows | V rows] buffers, each its own LDS object, and a tile loop
+    // unrolled by two: every access names its buffer statically, so the compiler
+    // knows that operand reads never touch the buffer an asynchronous load is
+    // filling.  K and V share an object so that the V operand address is the K
+    // operand address plus a constant.
+    __shared__ __align__(16) unsigned char lds_kv0[2][TILE_BYTES], lds_kv1[2][TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
@@ -147,23 +150,15 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
     zero_acc(acc);
     const float cs = prm.scale_log2;
 
-    __syncthreads();  // the previous pass is done with both buffers
-    ld.load(rk, lds_kv[0][0], 0, tid);
-    ld.load(rv, lds_kv[0][1], 0, tid);
-    wait_vmem();
-    __syncthreads();
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    auto do_tile = [&](int tile, const unsigned char *tk, unsigned char *nxt) __attribute__((always_inline)) {
         const int kv0 = tile * KT;
-        const unsigned char *tk = lds_kv[tile & 1][0];
         if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
-            ld.load(rk, lds_kv[(tile + 1) & 1][0], kv0 + KT, tid);
-            ld.load(rv, lds_kv[(tile + 1) & 1][1], kv0 + KT, tid);
+            ld.load(rk, nxt, kv0 + KT, tid);
+            ld.load(rv, nxt + TILE_BYTES, kv0 + KT, tid);
         }
         if (wave_active && kv0 <= w_pmax) {
             const bool diag = kv0 + KT - 1 > w_pmin;  // some key of the tile is past some query
-            // 32 keys at a time: S^T and dP^T stay in 32 registers.  The instruction
-            // order inside each half is pinned with scheduling groups so that LDS
-            // operand reads run a few MFMAs ahead of their use.
+            // 32 keys at a time: S^T and dP^T stay in 32 registers.
 #pragma unroll 1
             for (int jt = 0; jt < 2; ++jt) {
                 const unsigned char *th = tk + jt * (32 * TileGeom<D>::ROWB);  // this half's 32 keys
@@ -198,6 +193,16 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
         }
         wait_vmem();      // my share of the next tile has landed
         __syncthreads();  // ... and everyone's; everyone is done reading this tile
+    };
+
+    __syncthreads();  // the previous pass is done with both buffers
+    ld.load(rk, lds_kv0[0], 0, tid);
+    ld.load(rv, lds_kv0[1], 0, tid);
+    wait_vmem();
+    __syncthreads();
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        do_tile(tile, lds_kv0[0], lds_kv1[0]);
+        if (tile + 1 < n_tiles) do_tile(tile + 1, lds_kv1[0], lds_kv0[0]);
     }
     if (wave_active && my_i < rows) {
         // derived after the loop from opaque copies, so that no part of the
@@ -214,38 +219,41 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 //
 // One wave owning 32 key rows would need K, V, dK and dV of those rows in
 // registers (192 of them at d=128), which pins it to one wave per SIMD with
-// nothing to hide LDS latency or softmax arithmetic behind.  Here two waves that
-// share a SIMD share the 32 key rows instead:
+// nothing to hide LDS latency or softmax arithmetic behind.  Here two waves
+// share the 32 key rows instead:
 //   role 0 ("S wave"):  S = Q K^T, P = exp2(S*c - LSE'), dV^T += dO^T P;  holds K, dV
 //   role 1 ("dP wave"): dP = dO V^T, dS = P (dP - D), dK^T += Q^T dS;     holds V, dK
 // P goes from the first to the second through LDS in MFMA operand format (bf16,
-// 2 KB per 32x32 tile).  The dP wave runs one step behind, so that it always has
-// matrix work of its own (dP of step k) while the S wave does the softmax of
-// step k, and one workgroup barrier per step is all the synchronisation needed.
-// A step is 32 query rows; query tiles (64 rows) sit in a ring of three buffers
-// filled by asynchronous global->LDS loads two tiles ahead.
+// 4 KB per 64x32 tile).  The unit of work is a tile of 64 query rows; the dP
+// wave finishes a tile (dS, dK) one round after the S wave produced its P, so
+// one workgroup barrier per round is all the synchronisation there is, and in
+// every round both waves of a pair have 32 MFMAs of their own.
+// Query tiles (Q, dO, LSE', D) sit in a ring of three LDS slots: a round reads
+// the current slot (both waves) and the previous one (dP wave) while the
+// asynchronous fetch of the next tile fills the third.
 // ---------------------------------------------------------------------------
 constexpr int NWP = 8;  // 4 S waves + 4 dP waves
 
 template <int D>
-__global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams prm)
+__global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
 {
-    constexpr int NT = 64 * NWP, KS = D / 16, TT = D / 32, QT = TILE_ROWS;
-    constexpr int TILE_BYTES = TileGeom<D>::BYTES;
-    __shared__ __align__(16) unsigned char lds_t[3][2][TILE_BYTES];  // [ring][Q | dO] rows
-    __shared__ __align__(16) float lds_ld[3][2][QT];                 // [ring][LSE*log2e | D]
-    __shared__ __align__(16) unsigned char lds_p[4][2][2][1024];     // [pair][parity][half][lane*16]
+    constexpr int KS = D / 16, TT = D / 32, QT = TILE_ROWS;
+    constexpr int TB = TileGeom<D>::BYTES;
+    constexpr int SLOT = 2 * TB + 2 * QT * 4;  // Q rows | dO rows | LSE*log2e | D
+    __shared__ __align__(16) unsigned char lds_ring[3][SLOT];
+    __shared__ __align__(16) unsigned char lds_p[4][2][4][1024];  // [pair][round parity][16-row block][lane*16]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int role = wave >> 2, pw = wave & 3;  // waves w and w+4 share a SIMD and 32 key rows
+    const int role = wave >> 2, pw = wave & 3;  // waves w and w+4 share 32 key rows
     const int n = lane & 31, h = lane >> 5;
     const int item_id = blockIdx.x / prm.Hkv, c = blockIdx.x % prm.Hkv;
     const int g = prm.Hq / prm.Hkv;
     FragAddr<D> fa;
     fa.init(lane);
-    TileLoader<D, NT> ld;
-    ld.init(tid, (uint32_t)prm.Hq * D * 2);
+    RingLoader<D, NWP> ld;
+    ld.init(lane, wave, (uint32_t)prm.Hq * D * 2);
+    const uint32_t ring0 = lds_addr(&lds_ring[0][0]);
 
     const int4 it = prm.dkv_items[item_id];
     const int seq = it.x;
@@ -265,159 +273,198 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_pair_kernel(const BwdParams p
     bf16x8 bf[KS];
     {
         const uint16_t *src = role == 0 ? prm.k : prm.v;
-        int hh = h;
-        asm volatile("" : "+v"(hh));  // keep this address arithmetic inside the pass
-        const size_t off = ((size_t)(kbase + min(my_j, kvl - 1)) * prm.Hkv + c) * D + 8 * hh;
+        const size_t off = ((size_t)(kbase + min(my_j, kvl - 1)) * prm.Hkv + c) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bf[ks] = as_bf16x8(*(const uint4 *)(src + off + 16 * ks));
     }
 
     const int i_first = (max(0, kv0 - qb) / QT) * QT;  // first query tile that can see key kv0
     const int n_qt = (ql - i_first + QT - 1) / QT;
-    const int n_iter = n_qt * g;     // (head, query tile) pairs
-    const int n_steps = 2 * n_iter;  // 32-row steps
+    const int n_iter = n_qt * g;  // (head, query tile) pairs
 
     f32x16 acc[TT];  // dV^T (role 0) or dK^T (role 1) of this lane's key
     zero_acc(acc);
 
-    auto fetch = [&](int T) __attribute__((always_inline)) {
-        const int head = c * g + T / n_qt;
-        const int i0 = i_first + (T % n_qt) * QT;
-        const int buf = T % 3;
+    // fetch of tile (head th of the group, query tile tq_idx) into ring slot `slot`
+    auto fetch = [&](int th, int tq_idx, int slot) __attribute__((always_inline)) {
+        const int head = c * g + th;
+        const int i0 = i_first + tq_idx * QT;
+        const uint32_t base = ring0 + (uint32_t)slot * SLOT;
         const size_t hoff = ((size_t)qbase * prm.Hq + head) * D;
-        // query rows past the end of the sequence read as zero (and are masked)
-        ld.load(ld.rsrc(prm.q + hoff, ql), lds_t[buf][0], i0, tid);
-        ld.load(ld.rsrc(prm.d_o + hoff, ql), lds_t[buf][1], i0, tid);
-        if (wave < 2) {
-            typedef void __attribute__((address_space(3))) * lds_void_t;
-            const float *src = (wave == 0 ? prm.lse2 : prm.delta) + (size_t)head * prm.total_q +
-                               qbase + min(i0 + lane, ql - 1);
-            __builtin_amdgcn_global_load_lds((const void *)src, (lds_void_t)lds_ld[buf][wave], 4, 0, 0);
-        }
+        // rows past the end of the sequence read as zero (and are masked)
+        ld.load(ld.rsrc(prm.q + hoff, ql), base, i0, wave);
+        ld.load(ld.rsrc(prm.d_o + hoff, ql), base + TB, i0, wave);
+        const size_t soff = (size_t)head * prm.total_q + qbase;
+        if (wave == 2) dma_b32(rsrc_words(prm.lse2 + soff, (uint32_t)ql * 4), base + 2 * TB, lane * 4, i0 * 4);
+        if (wave == 3) dma_b32(rsrc_words(prm.delta + soff, (uint32_t)ql * 4), base + 2 * TB + QT * 4, lane * 4, i0 * 4);
     };
 
     __syncthreads();  // the previous pass is done with every buffer
-    fetch(0);
-    if (n_iter > 1) fetch(1);
+    fetch(0, 0, 0);
     wait_vmem();
     __syncthreads();
 
-    f32x16 dp_prev;  // role 1: dP of the previous step
-#pragma unroll
-    for (int v = 0; v < 16; ++v) dp_prev[v] = 0.0f;
-    bool prev_act = false;
-    int prev_buf = 0, prev_half = 0;
-
-    for (int k = 0; k <= n_steps; ++k) {  // the extra step drains the dP waves
-        const int T = k >> 1, half = k & 1, buf = T % 3;
-        if (half == 1 && T + 2 < n_iter) fetch(T + 2);  // into the buffer tile T-1 has left
-        const int i0 = i_first + (T % n_qt) * QT + 32 * half;  // first query row of the step
-        // skip steps whose last query still precedes this pair's first key
-        const bool act = k < n_steps && wave_active && qb + i0 + 31 >= wj0;
-        const unsigned char *tq = lds_t[buf][0], *tdo = lds_t[buf][1];
-        unsigned char *px = lds_p[pw][k & 1][0];
-
-        if (role == 0) {
+    // The two roles run the same round structure (same fetches, same barriers)
+    // in separate loops, so that each keeps only its own values in registers.
+    // Round T: ring slot T % 3 holds tile T = (head ch, query tile cq); the fetch
+    // of tile T+1 = (nh, nq) goes to the next slot.
+    if (role == 0) {
+        int nh = 0, nq = 1, cq = 0, slot = 0;
+        if (nq == n_qt) { nq = 0; nh = 1; }
+        for (int T = 0; T <= n_iter; ++T) {
+            const int slot_next = slot == 2 ? 0 : slot + 1;
+            if (T + 1 < n_iter) fetch(nh, nq, slot_next);
+            const unsigned char *cur = lds_ring[slot];
+            const int i0 = i_first + cq * QT;  // first query row of the tile
+            // a tile is skipped when its last query still precedes this pair's first key
+            const bool act = T < n_iter && wave_active && qb + i0 + QT - 1 >= wj0;
             if (act) {
-                f32x16 s;
+                const unsigned char *tq = cur, *tdo = cur + TB;
+                const float *t_lse = (const float *)(cur + 2 * TB);
+                unsigned char *px = lds_p[pw][T & 1][0];
+                f32x16 s[2];
+                zero_acc(s);
+                // operand reads go out in two groups, each ahead of the MFMAs that use it;
+                // the two 32-row blocks give two independent accumulation chains
 #pragma unroll
-                for (int v = 0; v < 16; ++v) s[v] = 0.0f;
-                bf16x8 fr[KS];
+                for (int kh = 0; kh < 2; ++kh) {
+                    bf16x8 f0[KS / 2], f1[KS / 2];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) fr[ks] = fa.rows(tq, half, ks);
-                __builtin_amdgcn_sched_barrier(0);  // all operand reads in flight before the MFMAs
+                    for (int x = 0; x < KS / 2; ++x) {
+                        f0[x] = fa.rows(tq, 0, kh * (KS / 2) + x);
+                        f1[x] = fa.rows(tq, 1, kh * (KS / 2) + x);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) s = mfma32(fr[ks], bf[ks], s);
-                bf16x8 ft[2][TT];  // transposed dO fragments, fetched behind the softmax
+                    for (int x = 0; x < KS / 2; ++x) {
+                        s[0] = mfma32(f0[x], bf[kh * (KS / 2) + x], s[0]);
+                        s[1] = mfma32(f1[x], bf[kh * (KS / 2) + x], s[1]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                bf16x8 ft[TT];  // transposed dO fragments of the first 16 rows, fetched behind the softmax
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) ft[kb][tt] = fa.cols(tdo, tt, 2 * half + kb);
-                __builtin_amdgcn_sched_barrier(0);
-                const float *t_lse = lds_ld[buf][0] + 32 * half;
+                for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(tdo, tt, 0);
                 // masked pairs: key past the query (causal) or query row past the end
-                const bool need_mask = (qb + i0 < wj0 + 31) || (i0 + 32 > ql);
+                const bool need_mask = (qb + i0 < wj0 + 31) || (i0 + QT > ql);
 #pragma unroll
-                for (int vb = 0; vb < 4; ++vb) {
-                    const float4 l4 = *(const float4 *)(t_lse + 8 * vb + 4 * h);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                for (int b = 0; b < 2; ++b) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        s[4 * vb + e] = fast_exp2(__builtin_fmaf(s[4 * vb + e], cs, -lv[e]));
+                    for (int vb = 0; vb < 4; ++vb) {
+                        const float4 l4 = *(const float4 *)(t_lse + 32 * b + 8 * vb + 4 * h);
+                        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            s[b][4 * vb + e] = fast_exp2(__builtin_fmaf(s[b][4 * vb + e], cs, -lv[e]));
+                    }
                 }
                 if (need_mask) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int i = i0 + acc_row(v, h);
-                        s[v] = (my_j > qb + i || i >= ql) ? 0.0f : s[v];
-                    }
+                    for (int b = 0; b < 2; ++b)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int i = i0 + 32 * b + acc_row(v, h);
+                            s[b][v] = (my_j > qb + i || i >= ql) ? 0.0f : s[b][v];
+                        }
                 }
-                const bf16x8 pb0 = acc_to_b(s, 0), pb1 = acc_to_b(s, 1);
-                *(bf16x8 *)(px + lane * 16) = pb0;
-                *(bf16x8 *)(px + 1024 + lane * 16) = pb1;
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[0][tt], pb0, acc[tt]);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[1][tt], pb1, acc[tt]);
-            }
-        } else {
-            if (prev_act) {
-                // dS and dK of the previous step: P as the S wave of this pair left it
-                const unsigned char *tqp = lds_t[prev_buf][0];
-                bf16x8 ft[2][TT];  // transposed Q fragments of the previous step
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) ft[kb][tt] = fa.cols(tqp, tt, 2 * prev_half + kb);
-                const unsigned char *pp = lds_p[pw][(k - 1) & 1][0];
-                const uint4 p0 = *(const uint4 *)(pp + lane * 16);
-                const uint4 p1 = *(const uint4 *)(pp + 1024 + lane * 16);
-                const uint32_t pw32[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                const float *t_dlt = lds_ld[prev_buf][1] + 32 * prev_half;
-#pragma unroll
-                for (int vb = 0; vb < 4; ++vb) {
-                    const float4 d4 = *(const float4 *)(t_dlt + 8 * vb + 4 * h);
-                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int v = 4 * vb + e;
-                        const uint32_t w = pw32[v >> 1];
-                        const float p = __builtin_bit_cast(float, (v & 1) ? (w & 0xffff0000u) : (w << 16));
-                        dp_prev[v] = p * (dp_prev[v] - dd[e]);  // dS
-                    }
-                }
-                const bf16x8 db0 = acc_to_b(dp_prev, 0), db1 = acc_to_b(dp_prev, 1);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[0][tt], db0, acc[tt]);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[1][tt], db1, acc[tt]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) dp_prev[v] = 0.0f;
-            if (act) {  // dP of this step, consumed in the next one
-                bf16x8 fr[KS];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) fr[ks] = fa.rows(tdo, half, ks);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) dp_prev = mfma32(fr[ks], bf[ks], dp_prev);
+                for (int kbg = 0; kbg < 4; ++kbg) {
+                    const bf16x8 pb = acc_to_b(s[kbg >> 1], kbg & 1);
+                    *(bf16x8 *)(px + kbg * 1024 + lane * 16) = pb;
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[tt], pb, acc[tt]);
+                    if (kbg < 3) {
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(tdo, tt, kbg + 1);
+                    }
+                }
+            }
+            wait_vmem();      // my share of the next tile has landed
+            __syncthreads();  // ... and everyone's; P of this round is visible; the previous slot is free
+            slot = slot_next;
+            cq = nq;
+            if (++nq == n_qt) { nq = 0; ++nh; }
+        }
+    } else {
+        f32x16 dp[2];  // dP of the previous round's tile
+        zero_acc(dp);
+        bool prev_act = false;
+        int nh = 0, nq = 1, cq = 0, slot = 0;
+        if (nq == n_qt) { nq = 0; nh = 1; }
+        for (int T = 0; T <= n_iter; ++T) {  // the extra round finishes the last tile
+            const int slot_next = slot == 2 ? 0 : slot + 1, slot_prev = slot == 0 ? 2 : slot - 1;
+            if (T + 1 < n_iter) fetch(nh, nq, slot_next);
+            const unsigned char *cur = lds_ring[slot], *prv = lds_ring[slot_prev];
+            const int i0 = i_first + cq * QT;
+            const bool act = T < n_iter && wave_active && qb + i0 + QT - 1 >= wj0;
+            if (prev_act) {
+                // dS and dK of the previous round's tile: P as the S wave of this pair left it
+                const float *t_dlt = (const float *)(prv + 2 * TB) + QT;
+                const unsigned char *pp = lds_p[pw][(T - 1) & 1][0];
+                bf16x8 ft[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(prv, tt, 0);
+#pragma unroll
+                for (int kbg = 0; kbg < 4; ++kbg) {
+                    const int b = kbg >> 1, kb = kbg & 1;
+                    const uint4 p4 = *(const uint4 *)(pp + kbg * 1024 + lane * 16);
+                    const uint32_t pw32[4] = {p4.x, p4.y, p4.z, p4.w};
+                    f32x16 &dpb = dp[b];
+#pragma unroll
+                    for (int vb = 0; vb < 2; ++vb) {
+                        const float4 d4 = *(const float4 *)(t_dlt + 32 * b + 16 * kb + 8 * vb + 4 * h);
+                        const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int v = 8 * kb + 4 * vb + e;
+                            const uint32_t w = pw32[(4 * vb + e) >> 1];
+                            const float pv = __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
+                            dpb[v] = pv * (dpb[v] - dd[e]);  // dS
+                        }
+                    }
+                    const bf16x8 db = acc_to_b(dpb, kb);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[tt], db, acc[tt]);
+                    if (kbg < 3) {
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(prv, tt, kbg + 1);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (act) {  // dP of this round's tile, consumed in the next round
+                const unsigned char *tdo = cur + TB;
+                zero_acc(dp);
+#pragma unroll
+                for (int kh = 0; kh < 2; ++kh) {
+                    bf16x8 f0[KS / 2], f1[KS / 2];
+#pragma unroll
+                    for (int x = 0; x < KS / 2; ++x) {
+                        f0[x] = fa.rows(tdo, 0, kh * (KS / 2) + x);
+                        f1[x] = fa.rows(tdo, 1, kh * (KS / 2) + x);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int x = 0; x < KS / 2; ++x) {
+                        dp[0] = mfma32(f0[x], bf[kh * (KS / 2) + x], dp[0]);
+                        dp[1] = mfma32(f1[x], bf[kh * (KS / 2) + x], dp[1]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             prev_act = act;
-            prev_buf = buf;
-            prev_half = half;
+            wait_vmem();
+            __syncthreads();
+            slot = slot_next;
+            cq = nq;
+            if (++nq == n_qt) { nq = 0; ++nh; }
         }
-        if (half == 0) wait_vmem();  // the tile fetched one step ago has had a full step to land
-        __syncthreads();
     }
     if (wave_active && my_j < kvl) {
-        // the output address is derived here, after the loop, from an opaque copy
-        // of the row index so that nothing of it occupies registers during the loop
-        int row = kbase + my_j, hh = h;
-        asm volatile("" : "+v"(row), "+v"(hh));
-        const size_t off = ((size_t)row * prm.Hkv + c) * D;
-        if (role == 0) store_rows_bf16<TT>(prm.dv + off, acc, 1.0f, hh);
-        else store_rows_bf16<TT>(prm.dk + off, acc, prm.scale, hh);
+        const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
+        if (role == 0) store_rows_bf16<TT>(prm.dv + off, acc, 1.0f, h);
+        else store_rows_bf16<TT>(prm.dk + off, acc, prm.scale, h);
     }
     }  // pass
 }
@@ -435,7 +482,7 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const voi
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
     const int gq = p->n_fwd * p->Hq, gk = p->n_dkv * p->Hkv;
-    dkv_pair_kernel<D><<<gk, 64 * NWP, 0, st>>>(prm);
+    dkv_kernel<D><<<gk, 64 * NWP, 0, st>>>(prm);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);

@@ -48,8 +48,12 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     static_assert(KT == TILE_ROWS, "staging helpers assume 64-row tiles");
 
     constexpr int TILE_BYTES = TileGeom<D>::BYTES;
-    __shared__ __align__(16) unsigned char lds_k[2][TILE_BYTES];  // double-buffered
-    __shared__ __align__(16) unsigned char lds_v[2][TILE_BYTES];
+    // Two tile buffers, each its own LDS object, and a tile loop unrolled by two
+    // so that every access names its buffer statically: the compiler can then
+    // tell that the operand reads of one buffer never touch the buffer an
+    // asynchronous load is filling, and does not wait for that load first.
+    __shared__ __align__(16) unsigned char lds_k0[TILE_BYTES], lds_k1[TILE_BYTES];
+    __shared__ __align__(16) unsigned char lds_v0[TILE_BYTES], lds_v1[TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
@@ -105,17 +109,14 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     float m_run = -INFINITY, l_run = 0.0f;
     const float cs = prm.scale_log2;
 
-    __syncthreads();  // the previous pass is done with both buffers
-    ld.load(rk, lds_k[0], 0, tid);
-    ld.load(rv, lds_v[0], 0, tid);
-    wait_vmem();
-    __syncthreads();
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    // one key tile: start the fetch of the next one into the other buffer, then
+    // S^T, online softmax and O^T on the current one
+    auto do_tile = [&](int tile, const unsigned char *tk, const unsigned char *tv,
+                       unsigned char *nk, unsigned char *nv) __attribute__((always_inline)) {
         const int kv0 = tile * KT;
-        const unsigned char *tk = lds_k[tile & 1], *tv = lds_v[tile & 1];
-        if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
-            ld.load(rk, lds_k[(tile + 1) & 1], kv0 + KT, tid);
-            ld.load(rv, lds_v[(tile + 1) & 1], kv0 + KT, tid);
+        if (tile + 1 < n_tiles) {  // lands during the math below
+            ld.load(rk, nk, kv0 + KT, tid);
+            ld.load(rv, nv, kv0 + KT, tid);
         }
 
         if (wave_active && kv0 <= w_pmax) {
@@ -190,6 +191,16 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         }
         wait_vmem();      // my share of the next tile has landed
         __syncthreads();  // ... and everyone's; everyone is done reading this tile
+    };
+
+    __syncthreads();  // the previous pass is done with both buffers
+    ld.load(rk, lds_k0, 0, tid);
+    ld.load(rv, lds_v0, 0, tid);
+    wait_vmem();
+    __syncthreads();
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        do_tile(tile, lds_k0, lds_v0, lds_k1, lds_v1);
+        if (tile + 1 < n_tiles) do_tile(tile + 1, lds_k1, lds_v1, lds_k0, lds_v0);
     }
 
     if (wave_active) {

@@ -129,6 +129,80 @@ struct TileLoader {
     }
 };
 
+// ---------------------------------------------------------------------------
+// The same asynchronous tile fetch with the two instructions written out
+// (M0 <- LDS address; buffer load to LDS).  The compiler does not see these as
+// writes to LDS, so operand reads of OTHER ring slots are not made to wait for
+// a fetch in flight, whichever slot a run-time index selects; the kernels order
+// a slot's fetch and its reads themselves (wait_vmem + workgroup barrier).
+// ---------------------------------------------------------------------------
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// raw buffer descriptor words over `bytes` bytes at `base` (wave-uniform)
+__device__ __forceinline__ i32x4 rsrc_words(const void *base, uint32_t bytes)
+{
+    const uint64_t p = (uint64_t)base;
+    i32x4 r = {(int)__builtin_amdgcn_readfirstlane((uint32_t)p),
+               (int)(__builtin_amdgcn_readfirstlane((uint32_t)(p >> 32)) & 0xffff),
+               (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000};
+    return r;
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    typedef const unsigned char __attribute__((address_space(3))) * lds_cptr_t;
+    return (uint32_t)(uintptr_t)(lds_cptr_t)p;
+}
+
+// 64 lanes x 16 bytes -> LDS [lds .. lds+1024); lane l fetches from base + voff + soff
+__device__ __forceinline__ void dma_b128(i32x4 rsrc, uint32_t lds, int voff, int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+// 64 lanes x 4 bytes -> LDS [lds .. lds+256)
+__device__ __forceinline__ void dma_b32(i32x4 rsrc, uint32_t lds, int voff, int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+
+// Tile loader for NWV wavefronts: wave w issues the 64-slot groups w, w+NWV, ...
+// of the tile (17 groups at d=128, 9 at d=64), so every instruction runs with
+// all lanes on and the only per-lane state is one byte offset per group.
+template <int D, int NWV>
+struct RingLoader {
+    typedef TileGeom<D> G;
+    static constexpr int GROUPS = G::SLOTS / 64;
+    static constexpr int PER = (GROUPS + NWV - 1) / NWV;
+    static_assert(G::SLOTS % 64 == 0, "tile slots must fill whole wave instructions");
+    int voff[PER];
+    uint32_t pitch;
+
+    __device__ __forceinline__ void init(int lane, int wave, uint32_t row_pitch_bytes)
+    {
+        pitch = row_pitch_bytes;
+#pragma unroll
+        for (int x = 0; x < PER; ++x) {
+            const int P = (x * NWV + wave) * 64 + lane;
+            const int pos = P / G::SPR, c = P % G::SPR;
+            voff[x] = row_pos(pos & 63) * (int)row_pitch_bytes + (c < G::CH ? c * 16 : 0);
+        }
+    }
+    // descriptor over rows [0, valid_rows) of one head of a [rows, H, D] matrix
+    __device__ __forceinline__ i32x4 rsrc(const uint16_t *row0_head, int valid_rows) const
+    {
+        return rsrc_words(row0_head, (uint32_t)(valid_rows - 1) * pitch + D * 2);
+    }
+    __device__ __forceinline__ void load(i32x4 r, uint32_t lds, int first_row, int wave) const
+    {
+        const int soff = first_row * (int)pitch;
+#pragma unroll
+        for (int x = 0; x < PER; ++x)
+            if (x * NWV + wave < GROUPS) dma_b128(r, lds + (x * NWV + wave) * 1024, voff[x], soff);
+    }
+};
+
 // Wait until this wave's outstanding vector-memory loads (incl. loads to LDS) have landed.
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
