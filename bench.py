@@ -153,7 +153,7 @@ def main():
         "frac_of_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "config": {"workload": w.name, "num_seqs": len(w.seq_len), "total_q": Tq, "total_k": Tk,
                    "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "attended_pairs": pairs,
-                   "useful_flops_per_step": useful, "block_m": args.block_m or 128,
+                   "useful_flops_per_step": useful, "block_m": args.block_m or 256,
                    "block_n": args.block_n or 128, "fwd_items": n_fwd_items, "dkv_items": n_dkv_items,
                    "step": "plan + fwd + bwd", "ms_plan": round(t_plan / args.steps * 1e3, 4)},
         "roofline": roofline,

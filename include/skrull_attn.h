@@ -56,7 +56,7 @@ typedef struct {
     int32_t        num_kv_heads;  /* Hkv >= 1, Hq % Hkv == 0                                   */
     int32_t        head_dim;      /* 64 or 128                                                 */
     float          softmax_scale; /* finite, > 0; multiplies Q.K^T inside the kernels          */
-    int32_t        block_m;       /* query rows per work item: 64, 128 or 256; 0 = 128          */
+    int32_t        block_m;       /* query rows per work item: 64, 128 or 256; 0 = 256          */
     int32_t        block_n;       /* key rows per dK/dV work item: 64, 128 or 256; 0 = 128      */
 } skrull_attn_problem_t;
 

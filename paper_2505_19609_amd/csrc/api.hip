@@ -67,7 +67,7 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         return SKRULL_EINVAL;
     if (p->head_dim != 64 && p->head_dim != 128) return SKRULL_EINVAL;
     if (!(p->softmax_scale > 0.0f) || !isfinite(p->softmax_scale)) return SKRULL_EINVAL;
-    const int32_t BM = p->block_m == 0 ? 128 : p->block_m;
+    const int32_t BM = p->block_m == 0 ? 256 : p->block_m;
     const int32_t BN = p->block_n == 0 ? 128 : p->block_n;
     if ((BM != 64 && BM != 128 && BM != 256) || (BN != 64 && BN != 128 && BN != 256))
         return SKRULL_EINVAL;

@@ -4,20 +4,29 @@
 // paper's cost model (App. B.2), the thing its scheduler balances.
 //
 // One workgroup = one work item (a block of BM query rows of one sequence) x
-// one query head.  It has 4 wavefronts, each owning 32 query rows, so it covers
-// 128 rows at a time; a 256-row item is two such passes, a 64-row item leaves
-// two wavefronts to help with staging only.  The key / value prefix is
-// streamed in tiles of 64 rows through LDS.
+// one query head.  It has 8 wavefronts (two per SIMD), each owning 32 query
+// rows, so it covers 256 rows per pass.  The key / value prefix is streamed in
+// tiles of 64 rows through two rings of three LDS slots.
 //
 // Orientation (see mfma.h): every tile is computed TRANSPOSED so that the
 // query index is the MFMA column and therefore lane-local:
 //     S^T[j, i] = sum_t K[j,t] Q[i,t]          A = K tile (LDS), B = Q (registers)
 //     O^T[t, i] += sum_j V^T[t,j] P^T[j,i]     A = V^T tile (LDS), B = P^T (registers)
-// A lane holds one query's 16 scores per 32x32 tile, so the running max, the
+// A lane holds one query's 16 scores per 32x32 block, so the running max, the
 // running sum and the rescale of O are plain per-lane scalars, and the S^T
 // accumulator registers, once converted to bf16, ARE the B operand of the
-// second product (the contraction index j just has to be enumerated the same
-// way on the A side, which the V^T LDS layout takes care of).
+// second product.
+//
+// Software pipeline.  The unit is a half tile (32 keys).  Step j of a wave
+// issues, interleaved in one instruction stream,
+//     the 8 MFMAs of S^T(j+1), the 8 MFMAs of O^T += V^T(j-1) P^T(j-1),
+//     and the softmax arithmetic of half tile j,
+// so that the matrix pipe always has independent work while the vector ALU
+// does the exponentials, and LDS operand reads run three MFMA pairs ahead of
+// their use.  Steps that touch the start, the end or the causal diagonal of a
+// wave's key range take a plain, unpipelined path.
+#include <type_traits>
+
 #include "common.h"
 #include "mfma.h"
 #include "tiles.h"
@@ -36,24 +45,78 @@ struct FwdParams {
     float scale_log2;  // softmax_scale * log2(e)
 };
 
-constexpr int NW = 4;          // wavefronts per workgroup
-constexpr int SUB = 32 * NW;   // query rows per pass
+constexpr int NW = 8;          // wavefronts per workgroup
+constexpr int SUB = 32 * NW;   // query rows per workgroup (the largest block_m)
+constexpr int NSLOT = 3;       // ring slots per operand
+
+#define SB() __builtin_amdgcn_sched_barrier(0)
+
+// max / sum of a value over the two halves of the wavefront (lanes l and l ^ 32)
+// without going through LDS: two copies of x, the upper half of the first
+// swapped with the lower half of the second, then the two combined.  Written out
+// whole, with the two idle cycles the swap needs after a vector write of its
+// operands: the compiler's builtin for the swap hands back its first result for
+// both when given one value twice.
+__device__ __forceinline__ float max_halves(float x)
+{
+    float r, t;
+    asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %2\n\ts_nop 1\n\t"
+                 "v_permlane32_swap_b32 %0, %1\n\tv_max_f32 %0, %0, %1"
+                 : "=&v"(r), "=&v"(t) : "v"(x));
+    return r;
+}
+__device__ __forceinline__ float sum_halves(float x)
+{
+    float r, t;
+    asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %2\n\ts_nop 1\n\t"
+                 "v_permlane32_swap_b32 %0, %1\n\tv_add_f32 %0, %0, %1"
+                 : "=&v"(r), "=&v"(t) : "v"(x));
+    return r;
+}
+
+// Two scores -> two probabilities (exp2 of score * c - m), their sum added to
+// rs, and the packed bf16 pair.  Written out so that the seven instructions stay
+// where the kernel puts them, between the MFMAs of a pipelined step (plain
+// arithmetic would be moved to its first use, i.e. behind all of them).  Each
+// exponential has one instruction between it and the first use of its result,
+// which is what this target asks for after a transcendental.
+__device__ __forceinline__ uint32_t softmax_pair(float s0, float s1, float c, float m, float &rs)
+{
+    float t0, t1;
+    uint32_t pk;
+    asm volatile("v_fma_f32 %0, %4, %6, -%7\n\t"
+                 "v_fma_f32 %1, %5, %6, -%7\n\t"
+                 "v_exp_f32 %0, %0\n\t"
+                 "v_exp_f32 %1, %1\n\t"
+                 "v_add_f32 %3, %3, %0\n\t"
+                 "v_add_f32 %3, %3, %1\n\t"
+                 "v_cvt_pk_bf16_f32 %2, %0, %1"
+                 : "=&v"(t0), "=&v"(t1), "=v"(pk), "+v"(rs)
+                 : "v"(s0), "v"(s1), "s"(c), "v"(m));
+    return pk;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmem_le()
+{
+    static_assert(N >= 0 && N < 16, "immediate form");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
 
 template <int D>
 __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 {
-    constexpr int NT = 64 * NW;  // threads
     constexpr int KS = D / 16;   // MFMA k-steps of Q.K^T
     constexpr int TT = D / 32;   // 32-row tiles of O^T
     static_assert(KT == TILE_ROWS, "staging helpers assume 64-row tiles");
+    static_assert(KS == 2 * TT, "a step pairs one S MFMA with one O MFMA");
+    typedef TileGeom<D> G;
+    constexpr int TB = G::BYTES;
+    constexpr int HALF = 32 * G::ROWB;  // byte offset of a tile's second 32 rows
+    typedef RingLoader<D, NW> Loader;
 
-    constexpr int TILE_BYTES = TileGeom<D>::BYTES;
-    // Two tile buffers, each its own LDS object, and a tile loop unrolled by two
-    // so that every access names its buffer statically: the compiler can then
-    // tell that the operand reads of one buffer never touch the buffer an
-    // asynchronous load is filling, and does not wait for that load first.
-    __shared__ __align__(16) unsigned char lds_k0[TILE_BYTES], lds_k1[TILE_BYTES];
-    __shared__ __align__(16) unsigned char lds_v0[TILE_BYTES], lds_v1[TILE_BYTES];
+    __shared__ __align__(16) unsigned char lds_k[NSLOT][TB];
+    __shared__ __align__(16) unsigned char lds_v[NSLOT][TB];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
@@ -69,19 +132,23 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 
     FragAddr<D> fa;
     fa.init(lane);
-    TileLoader<D, NT> ld;
-    ld.init(tid, (uint32_t)prm.Hkv * D * 2);
+    Loader ld;
+    ld.init(lane, wave, (uint32_t)prm.Hkv * D * 2);
+    const uint32_t ring_k = lds_addr(&lds_k[0][0]), ring_v = lds_addr(&lds_v[0][0]);
+    // asynchronous loads this wave issues per tile (its share of the 64-slot groups)
+    const bool big_share = wave < Loader::GROUPS - (Loader::PER - 1) * NW;
 
     const int4 it = prm.items[item_id];
     const int seq = it.x;
     const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
     const int kbase = prm.cu_k[seq];
     const int item_rows = min(prm.BM, ql - it.y * prm.BM);
+    const float cs = prm.scale_log2;
 
-    for (int sub = 0; sub * SUB < item_rows; ++sub) {
-    const int row0 = it.y * prm.BM + sub * SUB;
-    const int qrow0 = it.z + sub * SUB;
-    const int rows = min(SUB, ql - row0);
+    // block_m is at most 256 = the rows one workgroup covers: one pass per item
+    const int row0 = it.y * prm.BM;
+    const int qrow0 = it.z;
+    const int rows = item_rows;
     const int p0 = qb + row0;  // global position of the pass's first query
     const int n_tiles = (p0 + rows + KT - 1) / KT;
 
@@ -91,129 +158,236 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const int my_pos = p0 + my_i;
     const int w_pmin = p0 + wrow0;
     const int w_pmax = p0 + min(wrow0 + 31, rows - 1);
+    // half tiles (32 keys) of this wave: 0..L hold a visible key, those below n_full only visible keys
+    const int L = wave_active ? w_pmax / 32 : -1;
+    const int n_full = wave_active ? (w_pmin + 1) / 32 : 0;
 
-    // Q fragments (B operand of S^T): this lane's query row, 8 head-dims per k-step.
+    // Q fragments (B operand of S^T): this lane's query row, 8 head-dims per k-step
+    // (loaded below, behind the first tile fetches)
     bf16x8 qf[KS];
+    const i32x4 rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+    const i32x4 rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+
+    f32x16 oacc[TT];
+    zero_acc(oacc);
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    // ---- softmax pieces ---------------------------------------------------
+    auto row_max = [&](const f32x16 &s) __attribute__((always_inline)) {
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int v = 2; v < 16; v += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[v]), s[v + 1]);
+        mx = max_halves(mx);
+        return fmaxf(m_run, mx * cs);
+    };
+    // rescale of the running sum and of O when some lane's maximum moved
+    auto finish = [&](float m_new, float rs) __attribute__((always_inline)) {
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+            const float alpha = fast_exp2(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) oacc[tt][v] *= alpha;
+        }
+        l_run += rs;
+        m_run = m_new;
+    };
+
+    // ---- pipelined step j: S(j+1) from kp, softmax(j) on s_in, O += V(j-1) P(j-1) from vp
+    // FIRST: first step of a period (reads its first operands itself and, at the
+    // end, those of the second step from kp2 / vp2); otherwise they are in kf / vf.
+    auto steady = [&](auto first_tag, const unsigned char *kp, const unsigned char *vp,
+                      const unsigned char *kp2, const unsigned char *vp2, const f32x16 &s_in,
+                      f32x16 &s_out, const bf16x8 (&p_in)[2], bf16x8 (&p_out)[2], bf16x8 (&kf)[4],
+                      bf16x8 (&vf)[4]) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        if (FIRST) {
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                kf[x] = fa.rows(kp, 0, x);
+                vf[x] = fa.cols(vp, x % TT, x / TT);
+            }
+        }
+        SB();
+        const float m_new = row_max(s_in);
+        float rs = 0.0f;
+        uint32_t pw[8];
+        SB();
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            if (i == 0) {
+                f32x16 z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                s_out = mfma32(kf[0], qf[0], z);
+            } else {
+                s_out = mfma32(kf[i % 4], qf[i], s_out);
+            }
+            oacc[i % TT] = mfma32(vf[i % 4], p_in[i / TT], oacc[i % TT]);
+            const int nx = i + 3;
+            if (nx < KS) {
+                kf[nx % 4] = fa.rows(kp, 0, nx);
+                vf[nx % 4] = fa.cols(vp, nx % TT, nx / TT);
+            } else if (FIRST) {
+                kf[nx % 4] = fa.rows(kp2, 0, nx - KS);
+                vf[nx % 4] = fa.cols(vp2, (nx - KS) % TT, (nx - KS) / TT);
+            }
+            // softmax of this step's share of the 16 scores
+#pragma unroll
+            for (int e = (16 * i) / KS; e < (16 * (i + 1)) / KS; e += 2)
+                pw[e >> 1] = softmax_pair(s_in[e], s_in[e + 1], cs, m_new, rs);
+            SB();
+        }
+        p_out[0] = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        p_out[1] = as_bf16x8(make_uint4(pw[4], pw[5], pw[6], pw[7]));
+        finish(m_new, rs);
+    };
+
+    // ---- plain step j with run-time guards (start, end and diagonal of the wave's range)
+    auto generic = [&](int j, const unsigned char *kp, const unsigned char *vp, const f32x16 &s_in,
+                       f32x16 &s_out, const bf16x8 (&p_in)[2], bf16x8 (&p_out)[2]) __attribute__((always_inline)) {
+        if (j - 1 >= 0 && j - 1 <= L) {  // O += V(j-1) P(j-1)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) oacc[tt] = mfma32(fa.cols(vp, tt, kb), p_in[kb], oacc[tt]);
+                SB();
+            }
+        }
+        if (j + 1 <= L) {  // S(j+1)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s_out[v] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s_out = mfma32(fa.rows(kp, 0, ks), qf[ks], s_out);
+                if (ks % 4 == 3) SB();
+            }
+        }
+        if (j >= 0 && j <= L) {  // softmax(j)
+            f32x16 s = s_in;
+            if (j >= n_full) {  // half tile touches the diagonal for this wave
+                // relative position from an opaque copy of the lane index: the sixteen
+                // per-register thresholds are formed here rather than kept for the whole kernel
+                int li = lane;
+                asm volatile("" : "+v"(li));
+                const int rel = p0 + wrow0 + (li & 31) - 32 * j - 4 * (li >> 5);  // my_pos - 32j - 4h
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[v] = (8 * (v >> 2) + (v & 3) > rel) ? -INFINITY : s[v];
+            }
+            const float m_new = row_max(s);
+            float rs = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                s[v] = fast_exp2(__builtin_fmaf(s[v], cs, -m_new));
+                rs += s[v];
+            }
+            p_out[0] = acc_to_b(s, 0);
+            p_out[1] = acc_to_b(s, 1);
+            finish(m_new, rs);
+        }
+    };
+
+    // fetch group of period t: K tile t+2 and V tile t+1 (tiles past the end read as zero)
+    auto fetch = [&](int t, int ks_slot, int vs_slot) __attribute__((always_inline)) {
+        ld.load(rk, ring_k + (uint32_t)ks_slot * TB, (t + 2) * KT, wave);
+        ld.load(rv, ring_v + (uint32_t)vs_slot * TB, (t + 1) * KT, wave);
+    };
+    // wait until only the newest fetch group of this wave is still in flight
+    auto wait_older = [&]() __attribute__((always_inline)) {
+        if (big_share) wait_vmem_le<2 * Loader::PER>();
+        else wait_vmem_le<2 * (Loader::PER - 1)>();
+    };
+
+    ld.load(rk, ring_k, 0, wave);  // K tile 0
+    fetch(-1, 1, 0);               // K tile 1, V tile 0
+
     {
         const uint16_t *qp =
             prm.q + ((size_t)(qrow0 + min(my_i, rows - 1)) * prm.Hq + head) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = as_bf16x8(*(const uint4 *)(qp + 16 * ks));
     }
-
-    const __amdgpu_buffer_rsrc_t rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
-    const __amdgpu_buffer_rsrc_t rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
-
-    f32x16 oacc[TT];
-    zero_acc(oacc);
-    float m_run = -INFINITY, l_run = 0.0f;
-    const float cs = prm.scale_log2;
-
-    // one key tile: start the fetch of the next one into the other buffer, then
-    // S^T, online softmax and O^T on the current one
-    auto do_tile = [&](int tile, const unsigned char *tk, const unsigned char *tv,
-                       unsigned char *nk, unsigned char *nv) __attribute__((always_inline)) {
-        const int kv0 = tile * KT;
-        if (tile + 1 < n_tiles) {  // lands during the math below
-            ld.load(rk, nk, kv0 + KT, tid);
-            ld.load(rv, nv, kv0 + KT, tid);
-        }
-
-        if (wave_active && kv0 <= w_pmax) {
-            f32x16 s[2];
-            zero_acc(s);
-            // operand fragments are read from LDS in groups ahead of the MFMAs that use them
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh) {
-                bf16x8 f0[KS / 2], f1[KS / 2];
-#pragma unroll
-                for (int x = 0; x < KS / 2; ++x) {
-                    f0[x] = fa.rows(tk, 0, kh * (KS / 2) + x);
-                    f1[x] = fa.rows(tk, 1, kh * (KS / 2) + x);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int x = 0; x < KS / 2; ++x) {  // two independent accumulation chains
-                    s[0] = mfma32(f0[x], qf[kh * (KS / 2) + x], s[0]);
-                    s[1] = mfma32(f1[x], qf[kh * (KS / 2) + x], s[1]);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // first transposed V fragments: their latency hides behind the softmax arithmetic
-            bf16x8 fv[TT];
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) fv[tt] = fa.cols(tv, tt, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (kv0 + KT - 1 > w_pmin) {  // tile touches the diagonal for this wave
-#pragma unroll
-                for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        s[jt][v] = (kv0 + 32 * jt + acc_row(v, h) > my_pos) ? -INFINITY : s[jt][v];
-            }
-            float mx = s[0][0];
-#pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[jt][v]);
-            mx = fmaxf(mx, xor32(mx));
-            const float m_new = fmaxf(m_run, mx * cs);
-            float rs = 0.0f;
-#pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float p = fast_exp2(__builtin_fmaf(s[jt][v], cs, -m_new));
-                    s[jt][v] = p;
-                    rs += p;
-                }
-            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {  // rescale only when a max moved
-                const float alpha = fast_exp2(m_run - m_new);
-                l_run *= alpha;
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[tt][v] *= alpha;
-            }
-            l_run += rs;
-            m_run = m_new;
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int kbg = 0; kbg < 4; ++kbg) {
-                const bf16x8 pb = acc_to_b(s[kbg >> 1], kbg & 1);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) oacc[tt] = mfma32(fv[tt], pb, oacc[tt]);
-                if (kbg < 3) {
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) fv[tt] = fa.cols(tv, tt, kbg + 1);
-                }
-            }
-        }
-        wait_vmem();      // my share of the next tile has landed
-        __syncthreads();  // ... and everyone's; everyone is done reading this tile
-    };
-
-    __syncthreads();  // the previous pass is done with both buffers
-    ld.load(rk, lds_k0, 0, tid);
-    ld.load(rv, lds_v0, 0, tid);
+    // Everything issued so far has to land here: the compiler's own count of
+    // outstanding loads must be zero before the loops, or the waits it places
+    // for these fragments would also wait for the tile fetches in flight.
     wait_vmem();
     __syncthreads();
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        do_tile(tile, lds_k0, lds_v0, lds_k1, lds_v1);
-        if (tile + 1 < n_tiles) do_tile(tile + 1, lds_k1, lds_v1, lds_k0, lds_v0);
+
+    f32x16 sx, sy;         // S of the current / next half tile, ping-pong
+    bf16x8 px[2], py[2];   // P of the previous / current half tile, ping-pong
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sx[v] = 0.0f; sy[v] = 0.0f; }
+    {
+        const uint4 z4 = make_uint4(0, 0, 0, 0);
+        px[0] = px[1] = py[0] = py[1] = as_bf16x8(z4);
     }
 
+    // Period t: steps 2t-1 and 2t, i.e. S of both halves of K tile t and the
+    // O update with both halves of V tile t-1.  K tile t sits in slot t % 3,
+    // V tile t-1 in slot (t-1) % 3; the fetch of K tile t+2 / V tile t+1 goes to
+    // the slots that K tile t-1 / V tile t-2 left at the last barrier.
+    int kslot = 0, vslot = 2;  // slots of K tile t and V tile t-1
+    // start of a period: issue its fetch group; end: wait for the previous group, barrier, advance
+    auto period_begin = [&](int t) __attribute__((always_inline)) {
+        const int kslot_f = kslot == 0 ? 2 : kslot - 1;  // (t+2) % 3
+        const int vslot_f = vslot == 0 ? 2 : vslot - 1;  // (t+1) % 3
+        const bool more = t + 1 < n_tiles;  // V tile t+1 exists (K tile t+2 may read as zero)
+        if (more) fetch(t, kslot_f, vslot_f);
+        return more;
+    };
+    auto period_end = [&](bool more) __attribute__((always_inline)) {
+        if (more) wait_older();  // my share of K tile t+1 / V tile t has landed
+        else wait_vmem();        // nothing newer in flight
+        __syncthreads();         // ... and everyone's; everyone is done with K tile t / V tile t-1
+        kslot = kslot == 2 ? 0 : kslot + 1;
+        vslot = vslot == 2 ? 0 : vslot + 1;
+    };
+    // periods whose two steps are fully inside the wave's unmasked range
+    const int t_steady_end = min((L - 1) / 2, (n_full - 1) / 2);  // last t with 2t+1 <= L and 2t < n_full
+    // one copy of the plain step, run for both halves of a period; its results
+    // are moved back so that a period always starts from sx / px
+    auto plain_period = [&](int t) __attribute__((always_inline)) {
+        const bool more = period_begin(t);
+        const unsigned char *tk = lds_k[kslot], *tv = lds_v[vslot];
+#pragma unroll 1
+        for (int hh = 0; hh < 2; ++hh) {
+            generic(2 * t - 1 + hh, tk + hh * HALF, tv + hh * HALF, sx, sy, px, py);
+            sx = sy;
+            px[0] = py[0];
+            px[1] = py[1];
+        }
+        period_end(more);
+    };
+    plain_period(0);
+    int t = 1;
+    // the pipelined loop proper: S and P ping-pong between two register sets
+    for (; t <= t_steady_end; ++t) {
+        const bool more = period_begin(t);
+        const unsigned char *tk = lds_k[kslot], *tv = lds_v[vslot];
+        bf16x8 kf[4], vf[4];  // operand fragments in flight
+        steady(std::true_type{}, tk, tv, tk + HALF, tv + HALF, sx, sy, px, py, kf, vf);
+        steady(std::false_type{}, tk + HALF, tv + HALF, tk, tv, sy, sx, py, px, kf, vf);
+        period_end(more);
+    }
+#pragma unroll 1
+    for (; t <= n_tiles; ++t) plain_period(t);
+
     if (wave_active) {
-        const float l_tot = l_run + xor32(l_run);
+        const float l_tot = sum_halves(l_run);
         const float inv = 1.0f / l_tot;
-        if (my_i < rows) {
-            store_rows_bf16<TT>(prm.o + ((size_t)(qrow0 + my_i) * prm.Hq + head) * D, oacc, inv, h);
-            if (h == 0)
-                prm.lse[(size_t)head * prm.total_q + qrow0 + my_i] =
+        // the output addresses are formed here, after the loop, from opaque copies,
+        // so that nothing of them occupies registers during the loop
+        int li = lane;
+        asm volatile("" : "+v"(li));
+        const int on = li & 31, oh = li >> 5, oi = wrow0 + on;
+        if (oi < rows) {
+            store_rows_bf16<TT>(prm.o + ((size_t)(qrow0 + oi) * prm.Hq + head) * D, oacc, inv, oh);
+            if (oh == 0)
+                prm.lse[(size_t)head * prm.total_q + qrow0 + oi] =
                     (m_run + __log2f(l_tot)) * 0.6931471805599453f;
         }
     }
-    }  // pass
 }
 
 template <int D>

@@ -19,7 +19,7 @@ def _check(oracle, S, N, R, Hq, Hkv, d, bm, bn):
     plan = B.skrull_attn_plan(S, N, R, Hq, Hkv, d, 0.1, bm, bn)
     desc = oracle.ranges(S, N, R)
     BM, BN = plan.block_m, plan.block_n
-    assert (BM, BN) == (bm or 128, bn or 128)
+    assert (BM, BN) == (bm or 256, bn or 128)
     assert plan.total_q == desc["total_q"] and plan.total_k == desc["total_k"]
     assert plan.attended_pairs == oracle.attended_pairs(desc)
     assert plan.useful_flops_fwd == 4 * plan.attended_pairs * d * Hq
