@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const uint16_t *__restrict__
     if (pair < n_pairs && (gid % CH) == 0) {
         const int64_t row = pair / Hq;
         const int32_t hh = (int32_t)(pair % Hq);
-        delta[(int64_t)hh * total_q + row] = acc;
+        delta[(int64_t)hh * total_q + row] = -acc;  // the kernels add it (dP - D as dP + (-D))
         // LSE in the exp2 domain, so the main kernels need no extra multiply
         lse2[(int64_t)hh * total_q + row] = lse[(int64_t)hh * total_q + row] * kLog2e;
     }
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
         }
     }
     const float lse2 = prm.lse2[(size_t)head * prm.total_q + my_row];
-    const float dlt = prm.delta[(size_t)head * prm.total_q + my_row];
+    const float dlt = -prm.delta[(size_t)head * prm.total_q + my_row];  // the workspace holds -D
 
     const __amdgpu_buffer_rsrc_t rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
     const __amdgpu_buffer_rsrc_t rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
@@ -232,6 +232,47 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 // the current slot (both waves) and the previous one (dP wave) while the
 // asynchronous fetch of the next tile fills the third.
 // ---------------------------------------------------------------------------
+// Vector-ALU pieces of the dK/dV kernel, written out so that they stay where the
+// kernel puts them: between the MFMAs of the next block (plain arithmetic would be
+// moved to its first use, behind all of them, and a wave that issues nothing but
+// vector instructions for a long stretch slows the MFMAs of the wave it shares a
+// SIMD with).
+// Four scores -> four probabilities exp2(s * c - l), packed to two bf16 pairs.  Every
+// exponential has an instruction between it and the first use of its result.
+__device__ __forceinline__ void p_quad(const float (&sv)[4], float c, const float4 &l, uint32_t &w0, uint32_t &w1)
+{
+    float t0, t1, t2, t3;
+    asm volatile("v_fma_f32 %0, %6, %10, -%11\n\t"
+                 "v_fma_f32 %1, %7, %10, -%12\n\t"
+                 "v_fma_f32 %2, %8, %10, -%13\n\t"
+                 "v_fma_f32 %3, %9, %10, -%14\n\t"
+                 "v_exp_f32 %0, %0\n\t"
+                 "v_exp_f32 %1, %1\n\t"
+                 "v_exp_f32 %2, %2\n\t"
+                 "v_exp_f32 %3, %3\n\t"
+                 "v_cvt_pk_bf16_f32 %4, %0, %1\n\t"
+                 "v_cvt_pk_bf16_f32 %5, %2, %3"
+                 : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(w0), "=&v"(w1)
+                 : "v"(sv[0]), "v"(sv[1]), "v"(sv[2]), "v"(sv[3]), "s"(c), "v"(l.x), "v"(l.y), "v"(l.z), "v"(l.w));
+}
+// Two packed bf16 P pairs times four (dP - D) values -> two packed bf16 dS pairs.
+__device__ __forceinline__ void ds_quad(uint32_t p01, uint32_t p23, const float (&g)[4], uint32_t &w0, uint32_t &w1)
+{
+    float t0, t1, t2, t3;
+    asm volatile("v_lshlrev_b32 %0, 16, %6\n\t"
+                 "v_and_b32 %1, 0xffff0000, %6\n\t"
+                 "v_lshlrev_b32 %2, 16, %7\n\t"
+                 "v_and_b32 %3, 0xffff0000, %7\n\t"
+                 "v_mul_f32 %0, %0, %8\n\t"
+                 "v_mul_f32 %1, %1, %9\n\t"
+                 "v_mul_f32 %2, %2, %10\n\t"
+                 "v_mul_f32 %3, %3, %11\n\t"
+                 "v_cvt_pk_bf16_f32 %4, %0, %1\n\t"
+                 "v_cvt_pk_bf16_f32 %5, %2, %3"
+                 : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(w0), "=&v"(w1)
+                 : "v"(p01), "v"(p23), "v"(g[0]), "v"(g[1]), "v"(g[2]), "v"(g[3]));
+}
+
 constexpr int NWP = 8;  // 4 S waves + 4 dP waves
 
 template <int D>
@@ -247,7 +288,11 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int role = wave >> 2, pw = wave & 3;  // waves w and w+4 share 32 key rows
     const int n = lane & 31, h = lane >> 5;
-    const int item_id = blockIdx.x / prm.Hkv, c = blockIdx.x % prm.Hkv;
+    // blockIdx -> (item, 128-key pass of the item, KV head); an item of block_n = 256
+    // key rows is two workgroups
+    const int passes = (prm.BN + SUB - 1) / SUB;
+    const int sub = blockIdx.x % passes;
+    const int item_id = (blockIdx.x / passes) / prm.Hkv, c = (blockIdx.x / passes) % prm.Hkv;
     const int g = prm.Hq / prm.Hkv;
     FragAddr<D> fa;
     fa.init(lane);
@@ -262,7 +307,7 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
     const int item_rows = min(prm.BN, kvl - it.y * prm.BN);
     const float cs = prm.scale_log2;
 
-    for (int sub = 0; sub * SUB < item_rows; ++sub) {
+    if (sub * SUB >= item_rows) return;  // (whole workgroup) this item has no second pass
     const int kv0 = it.y * prm.BN + sub * SUB;  // first key position of the pass
     const int krows = min(SUB, kvl - kv0);
     const int wj0 = kv0 + 32 * pw;              // this pair's first key position
@@ -299,7 +344,6 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
         if (wave == 3) dma_b32(rsrc_words(prm.delta + soff, (uint32_t)ql * 4), base + 2 * TB + QT * 4, lane * 4, i0 * 4);
     };
 
-    __syncthreads();  // the previous pass is done with every buffer
     fetch(0, 0, 0);
     wait_vmem();
     __syncthreads();
@@ -322,61 +366,121 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
                 const unsigned char *tq = cur, *tdo = cur + TB;
                 const float *t_lse = (const float *)(cur + 2 * TB);
                 unsigned char *px = lds_p[pw][T & 1][0];
-                f32x16 s[2];
-                zero_acc(s);
-                // operand reads go out in two groups, each ahead of the MFMAs that use it;
-                // the two 32-row blocks give two independent accumulation chains
-#pragma unroll
-                for (int kh = 0; kh < 2; ++kh) {
-                    bf16x8 f0[KS / 2], f1[KS / 2];
-#pragma unroll
-                    for (int x = 0; x < KS / 2; ++x) {
-                        f0[x] = fa.rows(tq, 0, kh * (KS / 2) + x);
-                        f1[x] = fa.rows(tq, 1, kh * (KS / 2) + x);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int x = 0; x < KS / 2; ++x) {
-                        s[0] = mfma32(f0[x], bf[kh * (KS / 2) + x], s[0]);
-                        s[1] = mfma32(f1[x], bf[kh * (KS / 2) + x], s[1]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                bf16x8 ft[TT];  // transposed dO fragments of the first 16 rows, fetched behind the softmax
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(tdo, tt, 0);
                 // masked pairs: key past the query (causal) or query row past the end
                 const bool need_mask = (qb + i0 < wj0 + 31) || (i0 + QT > ql);
+                f32x16 s[2];
+                bf16x8 fr[4];
+                // S of the first 32 rows; operand reads run three MFMAs ahead
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tq, 0, x);
 #pragma unroll
-                    for (int vb = 0; vb < 4; ++vb) {
-                        const float4 l4 = *(const float4 *)(t_lse + 32 * b + 8 * vb + 4 * h);
-                        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (ks == 0) {
+                        f32x16 z;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            s[b][4 * vb + e] = fast_exp2(__builtin_fmaf(s[b][4 * vb + e], cs, -lv[e]));
+                        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                        s[0] = mfma32(fr[0], bf[0], z);
+                    } else {
+                        s[0] = mfma32(fr[ks % 4], bf[ks], s[0]);
                     }
+                    const int nx = ks + 3;
+                    fr[nx % 4] = nx < KS ? fa.rows(tq, 0, nx) : fa.rows(tq, 1, nx - KS);
+                    SB();
                 }
-                if (need_mask) {
+                if (!need_mask) {
+                    // S of the second 32 rows with the probabilities of the first behind its
+                    // MFMAs, then dV of the first with the probabilities of the second
+                    uint32_t w[2][8];
+                    bf16x8 ft[4];
 #pragma unroll
-                    for (int b = 0; b < 2; ++b)
+                    for (int ks = 0; ks < KS; ++ks) {
+                        if (ks == 0) {
+                            f32x16 z;
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int i = i0 + 32 * b + acc_row(v, h);
-                            s[b][v] = (my_j > qb + i || i >= ql) ? 0.0f : s[b][v];
+                            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                            s[1] = mfma32(fr[(KS + 0) % 4], bf[0], z);
+                        } else {
+                            s[1] = mfma32(fr[(KS + ks) % 4], bf[ks], s[1]);
                         }
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                        const int nx = ks + 3;
+                        if (nx < KS) fr[(KS + nx) % 4] = fa.rows(tq, 1, nx);
+                        if (KS == 8 ? (ks % 2 == 1) : true) {
+                            const int vb = KS == 8 ? ks / 2 : ks;
+                            const float4 l4 = *(const float4 *)(t_lse + 8 * vb + 4 * h);
+                            const float sv[4] = {s[0][4 * vb], s[0][4 * vb + 1], s[0][4 * vb + 2], s[0][4 * vb + 3]};
+                            p_quad(sv, cs, l4, w[0][2 * vb], w[0][2 * vb + 1]);
+                        }
+                        if (ks >= KS - 3) ft[(ks - (KS - 3))] = fa.cols(tdo, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
+                        SB();
+                    }
+                    const bf16x8 pb0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
+                    const bf16x8 pb1 = as_bf16x8(make_uint4(w[0][4], w[0][5], w[0][6], w[0][7]));
+                    *(bf16x8 *)(px + 0 * 1024 + lane * 16) = pb0;
+                    *(bf16x8 *)(px + 1 * 1024 + lane * 16) = pb1;
+                    // dV of rows 0..31 (2 x TT MFMAs); probabilities of rows 32..63 behind them
 #pragma unroll
-                for (int kbg = 0; kbg < 4; ++kbg) {
-                    const bf16x8 pb = acc_to_b(s[kbg >> 1], kbg & 1);
-                    *(bf16x8 *)(px + kbg * 1024 + lane * 16) = pb;
+                    for (int m = 0; m < 2 * TT; ++m) {
+                        acc[m % TT] = mfma32(ft[m % 4], m < TT ? pb0 : pb1, acc[m % TT]);
+                        const int nx = m + 3;
+                        ft[nx % 4] = fa.cols(tdo, nx % TT, nx / TT);  // runs on into rows 32..63
+                        if (TT == 4 ? (m % 2 == 1) : true) {
+                            const int vb = TT == 4 ? m / 2 : m;
+                            const float4 l4 = *(const float4 *)(t_lse + 32 + 8 * vb + 4 * h);
+                            const float sv[4] = {s[1][4 * vb], s[1][4 * vb + 1], s[1][4 * vb + 2], s[1][4 * vb + 3]};
+                            p_quad(sv, cs, l4, w[1][2 * vb], w[1][2 * vb + 1]);
+                        }
+                        SB();
+                    }
+                    const bf16x8 pb2 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
+                    const bf16x8 pb3 = as_bf16x8(make_uint4(w[1][4], w[1][5], w[1][6], w[1][7]));
+                    *(bf16x8 *)(px + 2 * 1024 + lane * 16) = pb2;
+                    *(bf16x8 *)(px + 3 * 1024 + lane * 16) = pb3;
+                    // dV of rows 32..63
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[tt], pb, acc[tt]);
-                    if (kbg < 3) {
+                    for (int m = 2 * TT; m < 4 * TT; ++m) {
+                        acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? pb2 : pb3, acc[m % TT]);
+                        const int nx = m + 3;
+                        if (nx < 4 * TT) ft[nx % 4] = fa.cols(tdo, nx % TT, nx / TT);
+                        SB();
+                    }
+                } else {
+                    // tiles on the causal diagonal or at the end of the sequence: plain order
 #pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(tdo, tt, kbg + 1);
+                    for (int ks = 0; ks < KS; ++ks) {
+                        if (ks == 0) {
+                            f32x16 z;
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                            s[1] = mfma32(fr[(KS + 0) % 4], bf[0], z);
+                        } else {
+                            s[1] = mfma32(fr[(KS + ks) % 4], bf[ks], s[1]);
+                        }
+                        const int nx = ks + 3;
+                        if (nx < KS) fr[(KS + nx) % 4] = fa.rows(tq, 1, nx);
+                        SB();
+                    }
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                        for (int vb = 0; vb < 4; ++vb) {
+                            const float4 l4 = *(const float4 *)(t_lse + 32 * b + 8 * vb + 4 * h);
+                            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int i = i0 + 32 * b + 8 * vb + 4 * h + e;
+                                const float pv = fast_exp2(__builtin_fmaf(s[b][4 * vb + e], cs, -lv[e]));
+                                s[b][4 * vb + e] = (my_j > qb + i || i >= ql) ? 0.0f : pv;
+                            }
+                        }
+                    }
+                    SB();
+#pragma unroll
+                    for (int kbg = 0; kbg < 4; ++kbg) {
+                        const bf16x8 pb = acc_to_b(s[kbg >> 1], kbg & 1);
+                        *(bf16x8 *)(px + kbg * 1024 + lane * 16) = pb;
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(fa.cols(tdo, tt, kbg), pb, acc[tt]);
+                        SB();
                     }
                 }
             }
@@ -387,7 +491,7 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             if (++nq == n_qt) { nq = 0; ++nh; }
         }
     } else {
-        f32x16 dp[2];  // dP of the previous round's tile
+        f32x16 dp[2];  // dP - D of the previous round's tile
         zero_acc(dp);
         bool prev_act = false;
         int nh = 0, nq = 1, cq = 0, slot = 0;
@@ -398,59 +502,104 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             const unsigned char *cur = lds_ring[slot], *prv = lds_ring[slot_prev];
             const int i0 = i_first + cq * QT;
             const bool act = T < n_iter && wave_active && qb + i0 + QT - 1 >= wj0;
-            if (prev_act) {
-                // dS and dK of the previous round's tile: P as the S wave of this pair left it
-                const float *t_dlt = (const float *)(prv + 2 * TB) + QT;
-                const unsigned char *pp = lds_p[pw][(T - 1) & 1][0];
-                bf16x8 ft[TT];
+            const unsigned char *tdo = cur + TB;
+            const float *t_nd = (const float *)(cur + 2 * TB) + QT;  // -D of this round's tile
+            const unsigned char *pp = lds_p[pw][(T - 1) & 1][0];
+            // accumulator start of a 32-row block of dP: -D of its rows
+            auto neg_d = [&](int b) __attribute__((always_inline)) {
+                f32x16 z;
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(prv, tt, 0);
+                for (int vb = 0; vb < 4; ++vb) {
+                    const float4 d4 = *(const float4 *)(t_nd + 32 * b + 8 * vb + 4 * h);
+                    z[4 * vb] = d4.x; z[4 * vb + 1] = d4.y; z[4 * vb + 2] = d4.z; z[4 * vb + 3] = d4.w;
+                }
+                return z;
+            };
+            // dS of 16 rows (block b, half kb) of the previous tile from its P and dP - D
+            auto ds_half = [&](const uint4 &p4, const f32x16 &g, int kb, uint32_t (&w)[4]) __attribute__((always_inline)) {
+                const float g0[4] = {g[8 * kb], g[8 * kb + 1], g[8 * kb + 2], g[8 * kb + 3]};
+                const float g1[4] = {g[8 * kb + 4], g[8 * kb + 5], g[8 * kb + 6], g[8 * kb + 7]};
+                ds_quad(p4.x, p4.y, g0, w[0], w[1]);
+                ds_quad(p4.z, p4.w, g1, w[2], w[3]);
+            };
+            if (act && prev_act) {
+                // Both tiles live: dP of this tile's first 32 rows with dS of the previous
+                // tile's first 32 rows behind its MFMAs; dK of those rows with the second dS
+                // behind; then dK of the second rows and dP of this tile's second rows.
+                f32x16 dpn;
+                bf16x8 fr[4], ft[4];
+                uint32_t w[4][4];
+                const uint4 p0 = *(const uint4 *)(pp + 0 * 1024 + lane * 16);
+                const uint4 p1 = *(const uint4 *)(pp + 1 * 1024 + lane * 16);
 #pragma unroll
-                for (int kbg = 0; kbg < 4; ++kbg) {
-                    const int b = kbg >> 1, kb = kbg & 1;
-                    const uint4 p4 = *(const uint4 *)(pp + kbg * 1024 + lane * 16);
-                    const uint32_t pw32[4] = {p4.x, p4.y, p4.z, p4.w};
-                    f32x16 &dpb = dp[b];
+                for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 0, x);
+                dpn = neg_d(0);
 #pragma unroll
-                    for (int vb = 0; vb < 2; ++vb) {
-                        const float4 d4 = *(const float4 *)(t_dlt + 32 * b + 16 * kb + 8 * vb + 4 * h);
-                        const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                for (int ks = 0; ks < KS; ++ks) {
+                    dpn = mfma32(fr[ks % 4], bf[ks], dpn);
+                    const int nx = ks + 3;
+                    if (nx < KS) fr[nx % 4] = fa.rows(tdo, 0, nx);
+                    if (ks == (KS == 8 ? 1 : 0)) ds_half(p0, dp[0], 0, w[0]);
+                    if (ks == (KS == 8 ? 4 : 2)) ds_half(p1, dp[0], 1, w[1]);
+                    if (ks >= KS - 3) ft[ks - (KS - 3)] = fa.cols(prv, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
+                    SB();
+                }
+                const uint4 p2 = *(const uint4 *)(pp + 2 * 1024 + lane * 16);
+                const uint4 p3 = *(const uint4 *)(pp + 3 * 1024 + lane * 16);
+                const bf16x8 db0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
+                const bf16x8 db1 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int v = 8 * kb + 4 * vb + e;
-                            const uint32_t w = pw32[(4 * vb + e) >> 1];
-                            const float pv = __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
-                            dpb[v] = pv * (dpb[v] - dd[e]);  // dS
-                        }
-                    }
-                    const bf16x8 db = acc_to_b(dpb, kb);
+                for (int m = 0; m < 2 * TT; ++m) {
+                    acc[m % TT] = mfma32(ft[m % 4], m < TT ? db0 : db1, acc[m % TT]);
+                    const int nx = m + 3;
+                    ft[nx % 4] = fa.cols(prv, nx % TT, nx / TT);  // runs on into rows 32..63
+                    if (m == (TT == 4 ? 1 : 0)) ds_half(p2, dp[1], 0, w[2]);
+                    if (m == (TT == 4 ? 4 : 2)) ds_half(p3, dp[1], 1, w[3]);
+                    SB();
+                }
+                const bf16x8 db2 = as_bf16x8(make_uint4(w[2][0], w[2][1], w[2][2], w[2][3]));
+                const bf16x8 db3 = as_bf16x8(make_uint4(w[3][0], w[3][1], w[3][2], w[3][3]));
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(ft[tt], db, acc[tt]);
-                    if (kbg < 3) {
+                for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 1, x);
 #pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) ft[tt] = fa.cols(prv, tt, kbg + 1);
+                for (int m = 2 * TT; m < 4 * TT; ++m) {
+                    acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? db2 : db3, acc[m % TT]);
+                    const int nx = m + 3;
+                    if (nx < 4 * TT) ft[nx % 4] = fa.cols(prv, nx % TT, nx / TT);
+                    SB();
+                }
+                dp[0] = dpn;
+                dp[1] = neg_d(1);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    dp[1] = mfma32(fr[ks % 4], bf[ks], dp[1]);
+                    const int nx = ks + 3;
+                    if (nx < KS) fr[nx % 4] = fa.rows(tdo, 1, nx);
+                    SB();
+                }
+            } else {
+                if (prev_act) {  // dS and dK of the previous tile only (this tile is skipped, or the last round)
+#pragma unroll
+                    for (int kbg = 0; kbg < 4; ++kbg) {
+                        const uint4 p4 = *(const uint4 *)(pp + kbg * 1024 + lane * 16);
+                        uint32_t w[4];
+                        ds_half(p4, dp[kbg >> 1], kbg & 1, w);
+                        const bf16x8 db = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(fa.cols(prv, tt, kbg), db, acc[tt]);
+                        SB();
                     }
                 }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (act) {  // dP of this round's tile, consumed in the next round
-                const unsigned char *tdo = cur + TB;
-                zero_acc(dp);
+                if (act) {  // dP - D of this tile only (first round, or the previous tile was skipped)
 #pragma unroll
-                for (int kh = 0; kh < 2; ++kh) {
-                    bf16x8 f0[KS / 2], f1[KS / 2];
+                    for (int b = 0; b < 2; ++b) {
+                        dp[b] = neg_d(b);
 #pragma unroll
-                    for (int x = 0; x < KS / 2; ++x) {
-                        f0[x] = fa.rows(tdo, 0, kh * (KS / 2) + x);
-                        f1[x] = fa.rows(tdo, 1, kh * (KS / 2) + x);
+                        for (int ks = 0; ks < KS; ++ks) {
+                            dp[b] = mfma32(fa.rows(tdo, b, ks), bf[ks], dp[b]);
+                            if (ks % 4 == 3) SB();
+                        }
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int x = 0; x < KS / 2; ++x) {
-                        dp[0] = mfma32(f0[x], bf[kh * (KS / 2) + x], dp[0]);
-                        dp[1] = mfma32(f1[x], bf[kh * (KS / 2) + x], dp[1]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             prev_act = act;
@@ -466,7 +615,6 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
         if (role == 0) store_rows_bf16<TT>(prm.dv + off, acc, 1.0f, h);
         else store_rows_bf16<TT>(prm.dk + off, acc, prm.scale, h);
     }
-    }  // pass
 }
 
 template <int D>
@@ -481,7 +629,7 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const voi
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    const int gq = p->n_fwd * p->Hq, gk = p->n_dkv * p->Hkv;
+    const int gq = p->n_fwd * p->Hq, gk = p->n_dkv * p->Hkv * ((p->BN + SUB - 1) / SUB);
     dkv_kernel<D><<<gk, 64 * NWP, 0, st>>>(prm);
     e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -49,7 +49,6 @@ constexpr int NW = 8;          // wavefronts per workgroup
 constexpr int SUB = 32 * NW;   // query rows per workgroup (the largest block_m)
 constexpr int NSLOT = 3;       // ring slots per operand
 
-#define SB() __builtin_amdgcn_sched_barrier(0)
 
 // max / sum of a value over the two halves of the wavefront (lanes l and l ^ 32)
 // without going through LDS: two copies of x, the upper half of the first
@@ -74,25 +73,31 @@ __device__ __forceinline__ float sum_halves(float x)
     return r;
 }
 
-// Two scores -> two probabilities (exp2 of score * c - m), their sum added to
-// rs, and the packed bf16 pair.  Written out so that the seven instructions stay
-// where the kernel puts them, between the MFMAs of a pipelined step (plain
-// arithmetic would be moved to its first use, i.e. behind all of them).  Each
-// exponential has one instruction between it and the first use of its result,
-// which is what this target asks for after a transcendental.
-__device__ __forceinline__ uint32_t softmax_pair(float s0, float s1, float c, float m, float &rs)
+// Two scores -> two probabilities (exp2 of score * c - m), in two parts so that
+// each part can sit behind one MFMA of a pipelined step: part one is the two
+// multiply-adds and exponentials, part two adds the results to rs and packs
+// them to bf16.  Written out so that the instructions stay where the kernel puts
+// them (plain arithmetic would be moved to its first use, i.e. behind all the
+// MFMAs of the step).  Each exponential has an instruction between it and the
+// first use of its result, which is what this target asks for after a
+// transcendental.
+__device__ __forceinline__ void softmax_exp2(float s0, float s1, float c, float m, float &t0, float &t1)
 {
-    float t0, t1;
-    uint32_t pk;
-    asm volatile("v_fma_f32 %0, %4, %6, -%7\n\t"
-                 "v_fma_f32 %1, %5, %6, -%7\n\t"
+    asm volatile("v_fma_f32 %0, %2, %4, -%5\n\t"
+                 "v_fma_f32 %1, %3, %4, -%5\n\t"
                  "v_exp_f32 %0, %0\n\t"
-                 "v_exp_f32 %1, %1\n\t"
-                 "v_add_f32 %3, %3, %0\n\t"
-                 "v_add_f32 %3, %3, %1\n\t"
-                 "v_cvt_pk_bf16_f32 %2, %0, %1"
-                 : "=&v"(t0), "=&v"(t1), "=v"(pk), "+v"(rs)
+                 "v_exp_f32 %1, %1"
+                 : "=&v"(t0), "=&v"(t1)
                  : "v"(s0), "v"(s1), "s"(c), "v"(m));
+}
+__device__ __forceinline__ uint32_t softmax_sum_pack(float t0, float t1, float &ra, float &rb)
+{
+    uint32_t pk;
+    asm volatile("v_add_f32 %1, %1, %3\n\t"
+                 "v_add_f32 %2, %2, %4\n\t"
+                 "v_cvt_pk_bf16_f32 %0, %3, %4"
+                 : "=v"(pk), "+v"(ra), "+v"(rb)
+                 : "v"(t0), "v"(t1));
     return pk;
 }
 
@@ -211,11 +216,15 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         }
         SB();
         const float m_new = row_max(s_in);
-        float rs = 0.0f;
+        float rs0 = 0.0f, rs1 = 0.0f;
         uint32_t pw[8];
         SB();
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
+            // one MFMA, a few vector instructions, one MFMA, a few more: the vector
+            // work of this step's share of the 16 scores runs behind the matrix pipe
+            constexpr int EPS = 16 / KS;  // scores per step (2 or 4)
+            float t[EPS];
             if (i == 0) {
                 f32x16 z;
 #pragma unroll
@@ -224,7 +233,13 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
             } else {
                 s_out = mfma32(kf[i % 4], qf[i], s_out);
             }
+#pragma unroll
+            for (int e = 0; e < EPS; e += 2)
+                softmax_exp2(s_in[EPS * i + e], s_in[EPS * i + e + 1], cs, m_new, t[e], t[e + 1]);
+            SB();
             oacc[i % TT] = mfma32(vf[i % 4], p_in[i / TT], oacc[i % TT]);
+#pragma unroll
+            for (int e = 0; e < EPS; e += 2) pw[(EPS * i + e) >> 1] = softmax_sum_pack(t[e], t[e + 1], rs0, rs1);
             const int nx = i + 3;
             if (nx < KS) {
                 kf[nx % 4] = fa.rows(kp, 0, nx);
@@ -233,12 +248,9 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                 kf[nx % 4] = fa.rows(kp2, 0, nx - KS);
                 vf[nx % 4] = fa.cols(vp2, (nx - KS) % TT, (nx - KS) / TT);
             }
-            // softmax of this step's share of the 16 scores
-#pragma unroll
-            for (int e = (16 * i) / KS; e < (16 * (i + 1)) / KS; e += 2)
-                pw[e >> 1] = softmax_pair(s_in[e], s_in[e + 1], cs, m_new, rs);
             SB();
         }
+        const float rs = rs0 + rs1;
         p_out[0] = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
         p_out[1] = as_bf16x8(make_uint4(pw[4], pw[5], pw[6], pw[7]));
         finish(m_new, rs);

@@ -27,6 +27,9 @@
 
 constexpr int TILE_ROWS = 64;
 
+// nothing is scheduled across this point: pins the hand-made order of the steps
+#define SB() __builtin_amdgcn_sched_barrier(0)
+
 template <int D>
 struct TileGeom {
     static constexpr int CH = D / 8;           // 16-byte chunks of payload per row
