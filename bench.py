@@ -55,6 +55,20 @@ def cpu_baseline(w, np):
                       f"{oracle.attended_pairs(desc)} pairs), all {w.num_q_heads} query heads, fp64 fwd+bwd"}
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload`, as measured offline with
+    rocprofv3's FETCH_SIZE / WRITE_SIZE counters (scaled by a plain copy of known
+    size; the summary file gives the commands), or None if no summary is there."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 3 and f[0] == "traffic" and f[1] == kernel:
+            return int(float(f[2]))
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +79,9 @@ def main():
     ap.add_argument("--block-m", type=int, default=0)
     ap.add_argument("--block-n", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding across "
@@ -113,6 +130,12 @@ def main():
     for _ in range(args.warmup):
         step().destroy()
     torch.cuda.synchronize()
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     B.skrull_attn_profile(True)
     kms = np.zeros(4)
@@ -142,7 +165,8 @@ def main():
     dom = max(kernels, key=lambda n: kernels[n][0])
     ach = kernels[dom][1] / (kernels[dom][0] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                "traffic": measured_traffic(w.name, dom),
                 "kernel_ms": {"fwd": round(float(kms[0]), 4), "delta": round(float(kms[1]), 4),
                               "dkv": round(float(kms[2]), 4), "dq": round(float(kms[3]), 4)}}
     out = {

@@ -344,17 +344,21 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
         if (wave == 3) dma_b32(rsrc_words(prm.delta + soff, (uint32_t)ql * 4), base + 2 * TB + QT * 4, lane * 4, i0 * 4);
     };
 
-    fetch(0, 0, 0);
+    fetch(0, n_qt - 1, 0);
     wait_vmem();
     __syncthreads();
 
     // The two roles run the same round structure (same fetches, same barriers)
     // in separate loops, so that each keeps only its own values in registers.
-    // Round T: ring slot T % 3 holds tile T = (head ch, query tile cq); the fetch
-    // of tile T+1 = (nh, nq) goes to the next slot.
+    // Round T: ring slot T % 3 holds (head T % g, query tile n_qt - 1 - T / g): heads
+    // innermost, query tiles from the end of the sequence down to the block's
+    // diagonal.  Every workgroup of a sequence then starts at the same tile and the
+    // ones running together walk the same tiles at the same time, which is what
+    // lets the XCD's L2 serve most of their fetches.  (cq = tile of round T,
+    // (nh, nq) = head and tile of round T+1, fetched into the next slot.)
     if (role == 0) {
-        int nh = 0, nq = 1, cq = 0, slot = 0;
-        if (nq == n_qt) { nq = 0; nh = 1; }
+        int nh = 1, nq = n_qt - 1, cq = n_qt - 1, slot = 0;
+        if (nh == g) { nh = 0; --nq; }
         for (int T = 0; T <= n_iter; ++T) {
             const int slot_next = slot == 2 ? 0 : slot + 1;
             if (T + 1 < n_iter) fetch(nh, nq, slot_next);
@@ -488,14 +492,14 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             __syncthreads();  // ... and everyone's; P of this round is visible; the previous slot is free
             slot = slot_next;
             cq = nq;
-            if (++nq == n_qt) { nq = 0; ++nh; }
+            if (++nh == g) { nh = 0; --nq; }
         }
     } else {
         f32x16 dp[2];  // dP - D of the previous round's tile
         zero_acc(dp);
         bool prev_act = false;
-        int nh = 0, nq = 1, cq = 0, slot = 0;
-        if (nq == n_qt) { nq = 0; nh = 1; }
+        int nh = 1, nq = n_qt - 1, cq = n_qt - 1, slot = 0;
+        if (nh == g) { nh = 0; --nq; }
         for (int T = 0; T <= n_iter; ++T) {  // the extra round finishes the last tile
             const int slot_next = slot == 2 ? 0 : slot + 1, slot_prev = slot == 0 ? 2 : slot - 1;
             if (T + 1 < n_iter) fetch(nh, nq, slot_next);
@@ -607,7 +611,7 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             __syncthreads();
             slot = slot_next;
             cq = nq;
-            if (++nq == n_qt) { nq = 0; ++nh; }
+            if (++nh == g) { nh = 0; --nq; }
         }
     }
     if (wave_active && my_j < kvl) {
