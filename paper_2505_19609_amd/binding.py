@@ -12,12 +12,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libskrull_attn.so")
 
-SKRULL_OK, SKRULL_EINVAL, SKRULL_ENOMEM, SKRULL_EHIP, SKRULL_EUNSUPPORTED = 0, -1, -2, -3, -4
+SKRULL_OK, SKRULL_EINVAL, SKRULL_ENOMEM, SKRULL_EHIP, SKRULL_EUNSUPPORTED, SKRULL_ESCHED = 0, -1, -2, -3, -4, -5
 ARRAY_CU_Q, ARRAY_CU_K, ARRAY_Q_BEGIN, ARRAY_Q_LEN, ARRAY_KV_LEN, ARRAY_FWD_ITEMS, ARRAY_DKV_ITEMS = range(7)
 
 EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
                     "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_plan_destroy",
-                    "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read")
+                    "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read",
+                    "skrull_dacp_schedule", "skrull_dacp_rank_batch")
 
 
 class Problem(ctypes.Structure):
@@ -41,6 +42,10 @@ class PlanInfo(ctypes.Structure):
                 ("n_fwd_items", ctypes.c_int32), ("n_dkv_items", ctypes.c_int32),
                 ("attended_pairs", ctypes.c_int64), ("useful_flops_fwd", ctypes.c_int64),
                 ("useful_flops_bwd", ctypes.c_int64), ("bwd_workspace_bytes", ctypes.c_int64)]
+
+
+class FlopsModel(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int64), ("hidden_kv", ctypes.c_int64), ("batch", ctypes.c_int64)]
 
 
 class SkrullError(RuntimeError):
@@ -79,6 +84,13 @@ def lib():
         L.skrull_attn_profile.restype = ctypes.c_int
         L.skrull_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
         L.skrull_attn_profile_read.restype = ctypes.c_int
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.skrull_dacp_schedule.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32,
+                                           ctypes.POINTER(FlopsModel), i32p]
+        L.skrull_dacp_schedule.restype = ctypes.c_int
+        L.skrull_dacp_rank_batch.argtypes = [ctypes.c_int32, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
+                                             i32p, i32p, i32p, i32p, i32p]
+        L.skrull_dacp_rank_batch.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -181,3 +193,33 @@ def skrull_attn_profile_read():
     ms = (ctypes.c_float * 4)()
     _check(lib().skrull_attn_profile_read(ms))
     return [float(x) for x in ms]
+
+
+def skrull_dacp_schedule(seq_len, bucket_size, cp_degree, hidden, hidden_kv, batch=1) -> np.ndarray:
+    """ret[K]: the rank that keeps sequence k whole, or -1 if it is distributed.
+    Raises SkrullError(SKRULL_ESCHED) when the micro-batch does not fit."""
+    S = np.ascontiguousarray(seq_len, dtype=np.int32)
+    if S.ndim != 1:
+        raise SkrullError(SKRULL_EINVAL, "seq_len must be 1-D")
+    ret = np.zeros(S.shape[0], np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    model = FlopsModel(int(hidden), int(hidden_kv), int(batch))
+    _check(lib().skrull_dacp_schedule(int(S.shape[0]), S.ctypes.data_as(i32p), int(bucket_size),
+                                      int(cp_degree), ctypes.byref(model), ret.ctypes.data_as(i32p)))
+    return ret
+
+
+def skrull_dacp_rank_batch(seq_len, ret, cp_degree, rank):
+    """(seq_len, shard_degree, shard_index, source) of rank `rank`'s micro-batch."""
+    S = np.ascontiguousarray(seq_len, dtype=np.int32)
+    R = np.ascontiguousarray(ret, dtype=np.int32)
+    if S.ndim != 1 or S.shape != R.shape:
+        raise SkrullError(SKRULL_EINVAL, "seq_len / ret must be 1-D and equally long")
+    K = int(S.shape[0])
+    out = [np.zeros(max(K, 1), np.int32) for _ in range(4)]
+    n = ctypes.c_int32(0)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    _check(lib().skrull_dacp_rank_batch(K, S.ctypes.data_as(i32p), R.ctypes.data_as(i32p),
+                                        int(cp_degree), int(rank), *[o.ctypes.data_as(i32p) for o in out],
+                                        ctypes.byref(n)))
+    return tuple(o[:n.value].copy() for o in out)

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libskrull_attn.so")
-SOURCES = ["api.hip", "plan.hip", "fwd.hip", "bwd.hip"]
+SOURCES = ["api.hip", "plan.hip", "fwd.hip", "bwd.hip", "dacp.cpp"]
 # packed fp32 VALU ops are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -23,7 +23,7 @@ def _compile(src: str) -> str:
     spills cost bandwidth in the hot loops, and a partially spilled MFMA
     operand tuple has been seen to be reloaded incompletely by this compiler
     (wrong results), so spilling kernels are not allowed in the library."""
-    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
     r = subprocess.run(["hipcc", *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c",
                         os.path.join(CSRC, src), "-o", obj], stderr=subprocess.PIPE, text=True)
     if r.returncode != 0:

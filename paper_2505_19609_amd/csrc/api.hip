@@ -9,6 +9,7 @@
 #include <new>
 
 #include "common.h"
+#include "skrull_dacp.h"
 
 namespace {
 
@@ -275,6 +276,7 @@ const char *skrull_attn_strerror(int code)
     case SKRULL_ENOMEM: return "out of memory";
     case SKRULL_EHIP: snprintf(buf, sizeof buf, "HIP runtime error (%s)", g_err); return buf;
     case SKRULL_EUNSUPPORTED: return "no gfx950 (MI355X) device available";
+    case SKRULL_ESCHED: return "DACP scheduling error: the micro-batch does not fit the buckets";
     default: return "unknown error code";
     }
 }

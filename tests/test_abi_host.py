@@ -20,7 +20,8 @@ def B():
 
 def test_library_exports_every_declared_symbol(B):
     header = open(os.path.join(ROOT, "include", "skrull_attn.h")).read()
-    declared = set(re.findall(r"\b(skrull_attn_[a-z_]+)\s*\(", header))
+    header += open(os.path.join(ROOT, "include", "skrull_dacp.h")).read()
+    declared = set(re.findall(r"\b(skrull_(?:attn|dacp)_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTED_SYMBOLS)
     L = B.lib()
     for name in declared:
