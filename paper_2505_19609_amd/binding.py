@@ -64,6 +64,11 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run __graft_entry__.build() "
                                "(python -m paper_2505_19609_amd.build); there is no fallback path")
+        # PyTorch ships its own HIP runtime; loading it first lets this library's
+        # libamdhip64 dependency resolve to that same copy, so device pointers and
+        # streams made by torch are valid in our calls (two runtimes in one process
+        # do not see each other's devices).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp = ctypes.c_void_p
         L.skrull_attn_plan.argtypes = [ctypes.POINTER(Problem), vp, ctypes.POINTER(vp)]

@@ -128,3 +128,48 @@ def make_values(w: Workload, total_q: int, total_k: int) -> dict:
             x *= np.float32(w.q_prescale)
         out[name] = f32_to_bf16_bits(x)
     return out
+
+
+# The paper's Table 1: share of sequences below 1K / 4K / 8K / 32K / 128K tokens and
+# the longest sequence, per corpus.  The corpora themselves are not available here;
+# `table1_lengths` draws from a piecewise log-uniform density with exactly these shares.
+TABLE1_EDGES = (16, 1024, 4096, 8192, 32768, 131072)
+TABLE1 = {
+    "wikipedia": ((0.8788, 0.9934, 0.9992, 0.9999, 1.0), 78 * 1024),
+    "lmsyschat1m": ((0.8712, 0.9935, 0.9987, 0.9998, 0.9999), 1643 * 1024),
+    "chatqa2_long_sft": ((0.2192, 0.3148, 0.4043, 0.9986, 1.0), 99 * 1024),
+}
+
+# (hidden h, hidden_kv h_kv, query heads, key/value heads, head_dim) of the model shapes
+# the paper trains (Qwen2.5-0.5B, Qwen2.5-7B) and of Llama-3-8B.
+MODEL_SHAPES = {
+    "qwen2.5-0.5b": (896, 128, 14, 2, 64),
+    "qwen2.5-7b": (3584, 512, 28, 4, 128),
+    "llama-3-8b": (4096, 1024, 32, 8, 128),
+}
+
+
+def table1_lengths(rng, dataset: str, count: int | None = None, budget: int | None = None,
+                   longest: int | None = None):
+    """Sequence lengths with the Table 1 shares of `dataset`: a bucket is chosen with
+    the table's probability, the length log-uniformly inside it (the tail beyond 128K
+    reaches to the corpus' longest sequence, or to `longest`).  Draw `count` lengths,
+    or as many as fit a `budget` of tokens: the first draw that would overflow ends the
+    batch and is dropped (redrawn while the batch is still empty)."""
+    cdf, cap = TABLE1[dataset]
+    cap = min(cap, longest) if longest else cap
+    edges = list(TABLE1_EDGES) + [max(cap, TABLE1_EDGES[-1] + 1)]
+    out, left = [], budget
+    while (count is None or len(out) < count) and (left is None or left > 0):
+        u = rng.random()
+        b = int(np.searchsorted(np.asarray(cdf), u, side="right"))
+        lo, hi = edges[b], edges[b + 1]
+        L = int(min(np.exp(rng.uniform(np.log(lo), np.log(hi))), cap))
+        if left is not None:
+            if L > left:
+                if out:
+                    break
+                continue
+            left -= L
+        out.append(L)
+    return out
