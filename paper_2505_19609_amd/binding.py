@@ -18,7 +18,8 @@ ARRAY_CU_Q, ARRAY_CU_K, ARRAY_Q_BEGIN, ARRAY_Q_LEN, ARRAY_KV_LEN, ARRAY_FWD_ITEM
 EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
                     "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_plan_destroy",
                     "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read",
-                    "skrull_dacp_schedule", "skrull_dacp_rank_batch")
+                    "skrull_dacp_schedule", "skrull_dacp_rank_batch",
+                    "skrull_gds_binpack", "skrull_gds_schedule", "skrull_gds_micro_batch")
 
 
 class Problem(ctypes.Structure):
@@ -96,6 +97,13 @@ def lib():
         L.skrull_dacp_rank_batch.argtypes = [ctypes.c_int32, i32p, i32p, ctypes.c_int32, ctypes.c_int32,
                                              i32p, i32p, i32p, i32p, i32p]
         L.skrull_dacp_rank_batch.restype = ctypes.c_int
+        L.skrull_gds_binpack.argtypes = [ctypes.c_int32, i32p, ctypes.c_int32, ctypes.POINTER(FlopsModel), i32p]
+        L.skrull_gds_binpack.restype = ctypes.c_int
+        L.skrull_gds_schedule.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.POINTER(FlopsModel), i32p, i32p, i32p, i32p]
+        L.skrull_gds_schedule.restype = ctypes.c_int
+        L.skrull_gds_micro_batch.argtypes = [ctypes.c_int32, i32p, i32p, ctypes.c_int32, i32p, i32p]
+        L.skrull_gds_micro_batch.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -228,3 +236,50 @@ def skrull_dacp_rank_batch(seq_len, ret, cp_degree, rank):
                                         int(cp_degree), int(rank), *[o.ctypes.data_as(i32p) for o in out],
                                         ctypes.byref(n)))
     return tuple(o[:n.value].copy() for o in out)
+
+
+def _lengths(seq_len) -> np.ndarray:
+    S = np.ascontiguousarray(seq_len, dtype=np.int32)
+    if S.ndim != 1:
+        raise SkrullError(SKRULL_EINVAL, "seq_len must be 1-D")
+    return S
+
+
+def skrull_gds_binpack(seq_len, dp_world_size, hidden, hidden_kv, batch=1) -> np.ndarray:
+    """dp_bin[K]: the DP rank of every sequence of the global batch."""
+    S = _lengths(seq_len)
+    out = np.zeros(S.shape[0], np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    model = FlopsModel(int(hidden), int(hidden_kv), int(batch))
+    _check(lib().skrull_gds_binpack(int(S.shape[0]), S.ctypes.data_as(i32p), int(dp_world_size),
+                                    ctypes.byref(model), out.ctypes.data_as(i32p)))
+    return out
+
+
+def skrull_gds_schedule(seq_len, bucket_size, cp_degree, dp_world_size, dp_rank, hidden, hidden_kv, batch=1):
+    """(dp_bin[K], micro_batch[K], ret[K], num_micro_batches) for DP rank `dp_rank`."""
+    S = _lengths(seq_len)
+    K = int(S.shape[0])
+    bins, mb, ret = (np.zeros(K, np.int32) for _ in range(3))
+    n = ctypes.c_int32(0)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    model = FlopsModel(int(hidden), int(hidden_kv), int(batch))
+    _check(lib().skrull_gds_schedule(K, S.ctypes.data_as(i32p), int(bucket_size), int(cp_degree),
+                                     int(dp_world_size), int(dp_rank), ctypes.byref(model),
+                                     bins.ctypes.data_as(i32p), mb.ctypes.data_as(i32p),
+                                     ret.ctypes.data_as(i32p), ctypes.byref(n)))
+    return bins, mb, ret, int(n.value)
+
+
+def skrull_gds_micro_batch(seq_len, micro_batch, index) -> np.ndarray:
+    """Positions (caller's list) of the members of micro-batch `index`, ascending length."""
+    S = _lengths(seq_len)
+    M = np.ascontiguousarray(micro_batch, dtype=np.int32)
+    if M.shape != S.shape:
+        raise SkrullError(SKRULL_EINVAL, "seq_len / micro_batch must be equally long")
+    out = np.zeros(max(int(S.shape[0]), 1), np.int32)
+    n = ctypes.c_int32(0)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    _check(lib().skrull_gds_micro_batch(int(S.shape[0]), S.ctypes.data_as(i32p), M.ctypes.data_as(i32p),
+                                        int(index), out.ctypes.data_as(i32p), ctypes.byref(n)))
+    return out[:n.value].copy()

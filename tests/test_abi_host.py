@@ -19,9 +19,9 @@ def B():
 
 
 def test_library_exports_every_declared_symbol(B):
-    header = open(os.path.join(ROOT, "include", "skrull_attn.h")).read()
-    header += open(os.path.join(ROOT, "include", "skrull_dacp.h")).read()
-    declared = set(re.findall(r"\b(skrull_(?:attn|dacp)_[a-z_]+)\s*\(", header))
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
+    declared = set(re.findall(r"\b(skrull_(?:attn|dacp|gds)_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTED_SYMBOLS)
     L = B.lib()
     for name in declared:
