@@ -74,24 +74,33 @@ def num_threads() -> int:
 # --------------------------------------------------------------------------
 # integer part
 # --------------------------------------------------------------------------
-def ranges(seq_len, shard_degree=None, shard_index=None) -> dict:
-    """Per-sequence query/KV ranges and packed offsets (paper Eq. 8 slices)."""
+def ranges(seq_len, shard_degree=None, shard_index=None, shard_cut=None) -> dict:
+    """Query segments and packed offsets (paper Eq. 8 slices).  A sequence cut the
+    contiguous way (shard_cut 0, the default) is one segment; one cut the load-balanced
+    way (shard_cut 1: chunks r and 2N-1-r of 2N) is two consecutive segments that share
+    one key/value prefix.  Every array of the result is per SEGMENT."""
     S = _i32(seq_len)
     K = S.shape[0]
     N = _i32(np.ones(K) if shard_degree is None else shard_degree)
     r = _i32(np.zeros(K) if shard_index is None else shard_index)
-    out = {n: np.zeros(K, np.int32) for n in ("q_begin", "q_len", "kv_len")}
-    out["cu_q"] = np.zeros(K + 1, np.int32)
-    out["cu_k"] = np.zeros(K + 1, np.int32)
-    rc = _load().oracle_ranges(ctypes.c_int32(K), _p(S, _i32p), _p(N, _i32p), _p(r, _i32p),
+    z = _i32(np.zeros(K) if shard_cut is None else shard_cut)
+    out = {n: np.zeros(2 * K, np.int32) for n in ("q_begin", "q_len", "kv_len", "shares_kv")}
+    out["cu_q"] = np.zeros(2 * K + 1, np.int32)
+    out["cu_k"] = np.zeros(2 * K + 1, np.int32)
+    ns = _load().oracle_ranges(ctypes.c_int32(K), _p(S, _i32p), _p(N, _i32p), _p(r, _i32p),
+                               _p(z, _i32p),
                                _p(out["q_begin"], _i32p), _p(out["q_len"], _i32p),
                                _p(out["kv_len"], _i32p), _p(out["cu_q"], _i32p),
-                               _p(out["cu_k"], _i32p))
-    if rc != 0:
+                               _p(out["cu_k"], _i32p), _p(out["shares_kv"], _i32p))
+    if ns < 0:
         raise ValueError("oracle_ranges: invalid problem")
-    out["num_seqs"] = K
-    out["total_q"] = int(out["cu_q"][K])
-    out["total_k"] = int(out["cu_k"][K])
+    for n in ("q_begin", "q_len", "kv_len", "shares_kv"):
+        out[n] = np.ascontiguousarray(out[n][:ns])
+    out["cu_q"] = np.ascontiguousarray(out["cu_q"][:ns + 1])
+    out["cu_k"] = np.ascontiguousarray(out["cu_k"][:ns + 1])
+    out["num_seqs"] = ns          # number of segments: the length of the arrays above
+    out["total_q"] = int(out["cu_q"][ns])
+    out["total_k"] = int(out["cu_k"][ns])
     return out
 
 
@@ -117,7 +126,7 @@ def dkv_items(desc: dict, block_m: int, block_n: int) -> np.ndarray:
     lib = _load()
     K = ctypes.c_int32(desc["num_seqs"])
     args = (K, _p(desc["q_begin"], _i32p), _p(desc["q_len"], _i32p), _p(desc["kv_len"], _i32p),
-            ctypes.c_int32(block_m), ctypes.c_int32(block_n))
+            _p(desc["shares_kv"], _i32p), ctypes.c_int32(block_m), ctypes.c_int32(block_n))
     n = lib.oracle_dkv_items(*args, None)
     items = np.zeros((n, 4), np.int32)
     lib.oracle_dkv_items(*args, _p(items, _i32p))
@@ -262,6 +271,7 @@ def attention_bwd(q, k, v, do, desc, scale):
     crow = desc["cu_k"][cent[0]] + cent[2]
     dK = np.zeros((Tk, Hkv, d), np.float64)
     dV = np.zeros((Tk, Hkv, d), np.float64)
-    dK[crow, cent[1]] = dk
-    dV[crow, cent[1]] = dv
+    # += : two segments that share a key/value prefix both contribute to its rows
+    np.add.at(dK, (crow, cent[1]), dk)
+    np.add.at(dV, (crow, cent[1]), dv)
     return dQ, dK, dV, D

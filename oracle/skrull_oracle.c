@@ -23,7 +23,9 @@
  * Readings the paper leaves open (each also listed in the design notes):
  *  - the slice of a distributed sequence is the CONTIGUOUS query range
  *    [floor(r*S/N), floor((r+1)*S/N)) of shard index r, attending to the key /
- *    value prefix [0, q_end) at its true global positions;
+ *    value prefix [0, q_end) at its true global positions; or, as a
+ *    load-balanced alternative, chunks r and 2N-1-r of a cut into 2N chunks
+ *    (see oracle_ranges);
  *  - query head h reads key/value head h / (Hq/Hkv) (contiguous GQA groups);
  *  - LSE is the natural log of the sum of exp(scale * q.k) over allowed keys.
  *
@@ -45,34 +47,59 @@
 /* Integer part                                                        */
 /* ------------------------------------------------------------------ */
 
-/* Per-sequence ranges and packed offsets (paper Eq. 8: a distributed sequence
+/* Query segments and packed offsets (paper Eq. 8: a distributed sequence
  * contributes S_k/N tokens to each rank; local ones contribute S_k).
- *   q_begin = floor(r*S/N), q_end = floor((r+1)*S/N), q_len = q_end - q_begin,
- *   kv_len = q_end; cu_q / cu_k are exclusive prefix sums with a total at [K].
- * Returns 0, or -1 on an invalid entry (S<1, N<1, r outside [0,N), N>S) or if a
- * total does not fit in int32. */
+ *
+ * cut[k] = 0: ONE segment, the contiguous slice of shard index r:
+ *   q_begin = floor(r*S/N), q_end = floor((r+1)*S/N), kv_len = q_end.
+ * cut[k] = 1 (load-balanced cut; the paper leaves the cut open and its Eq. 4
+ *   assumes every rank does 1/N of the work, which a causal contiguous cut does
+ *   not give): the sequence is cut into 2N chunks [floor(i*S/2N), floor((i+1)*S/2N));
+ *   the rank holds chunk r and chunk 2N-1-r, as TWO consecutive segments (early
+ *   chunk first) whose query rows follow each other in Q/O/dQ/dO and which share
+ *   ONE key/value prefix [0, end of the late chunk): cu_k is the same for both,
+ *   shares_kv[late segment] = 1.
+ * A segment is all the other functions here know: query rows q_begin..q_begin+q_len-1
+ * (global positions) at packed rows cu_q.., seeing keys 0..position at packed rows
+ * cu_k..; kv_len = q_begin + q_len.
+ * Outputs have room for 2K segments (cu_q / cu_k: 2K+1; the entry after the last
+ * segment holds the total).  Returns the number of segments, or -1 on an invalid
+ * entry (S<1, N<1, r outside [0,N), fewer tokens than chunks, cut not 0/1) or if a
+ * total does not fit in int32.  cut may be NULL (all 0). */
 int oracle_ranges(int32_t K, const int32_t *S, const int32_t *N, const int32_t *r,
+                  const int32_t *cut,
                   int32_t *q_begin, int32_t *q_len, int32_t *kv_len,
-                  int32_t *cu_q, int32_t *cu_k)
+                  int32_t *cu_q, int32_t *cu_k, int32_t *shares_kv)
 {
     int64_t tq = 0, tk = 0;
+    int32_t ns = 0;
     if (K < 1) return -1;
-    cu_q[0] = 0;
-    cu_k[0] = 0;
     for (int32_t k = 0; k < K; ++k) {
-        if (S[k] < 1 || N[k] < 1 || r[k] < 0 || r[k] >= N[k] || N[k] > S[k]) return -1;
-        int64_t b = ((int64_t)r[k] * (int64_t)S[k]) / (int64_t)N[k];
-        int64_t e = ((int64_t)(r[k] + 1) * (int64_t)S[k]) / (int64_t)N[k];
-        q_begin[k] = (int32_t)b;
-        q_len[k] = (int32_t)(e - b);
-        kv_len[k] = (int32_t)e;
-        tq += e - b;
-        tk += e;
+        const int32_t z = cut ? cut[k] : 0;
+        if (z != 0 && z != 1) return -1;
+        const int64_t chunks = (int64_t)N[k] * (z ? 2 : 1);
+        if (S[k] < 1 || N[k] < 1 || r[k] < 0 || r[k] >= N[k] || chunks > S[k]) return -1;
+        const int64_t idx[2] = {r[k], 2 * (int64_t)N[k] - 1 - r[k]};
+        int64_t owned = 0;
+        for (int32_t part = 0; part <= z; ++part) {
+            const int64_t b = (idx[part] * (int64_t)S[k]) / chunks;
+            const int64_t e = ((idx[part] + 1) * (int64_t)S[k]) / chunks;
+            q_begin[ns] = (int32_t)b;
+            q_len[ns] = (int32_t)(e - b);
+            kv_len[ns] = (int32_t)e;
+            cu_q[ns] = (int32_t)tq;
+            cu_k[ns] = (int32_t)tk;
+            shares_kv[ns] = part;
+            tq += e - b;
+            owned = e;              /* the late chunk's prefix covers the early one's */
+            ++ns;
+        }
+        tk += owned;
         if (tq > INT32_MAX || tk > INT32_MAX) return -1;
-        cu_q[k + 1] = (int32_t)tq;
-        cu_k[k + 1] = (int32_t)tk;
     }
-    return 0;
+    cu_q[ns] = (int32_t)tq;
+    cu_k[ns] = (int32_t)tk;
+    return ns;
 }
 
 /* Number of attended (query, key) pairs: query at global position p sees keys
@@ -140,27 +167,37 @@ int32_t oracle_fwd_items(int32_t K, const int32_t *q_begin, const int32_t *q_len
     return n;
 }
 
-/* dK/dV work list.  One item per (sequence k, key block n of BN rows):
- *   {k, n, m0, n_q}: the first local query row that can see the block is
- *   i0 = max(0, n*BN - q_begin); m0 = floor(i0 / BM) is the first query block
- *   that touches it and n_q = ceil(q_len/BM) - m0 the number that do (cost).
+/* dK/dV work list.  One item per (key/value prefix, key block n of BN rows).  A
+ * prefix belongs to the LAST segment k that reads it (the only one, or the late chunk
+ * of a two-chunk cut); an early chunk (shares_kv[k+1] = 1) emits no items of its own.
+ *   {k, n, m0, n_q}: the first local query row of segment k that can see the block is
+ *   i0 = max(0, n*BN - q_begin); m0 = floor(i0 / BM) is its first query block that
+ *   touches it; n_q (cost) = the number of query blocks that do: ceil(q_len/BM) - m0
+ *   of segment k plus, if the prefix is shared and the block starts inside the early
+ *   chunk's own prefix, the same count for segment k-1.
  * Same emission order and the same stable descending sort as above. */
 int32_t oracle_dkv_items(int32_t K, const int32_t *q_begin, const int32_t *q_len,
-                         const int32_t *kv_len, int32_t BM, int32_t BN, int32_t *items)
+                         const int32_t *kv_len, const int32_t *shares_kv,
+                         int32_t BM, int32_t BN, int32_t *items)
 {
     int32_t n = 0;
     for (int32_t k = 0; k < K; ++k) {
+        if (k + 1 < K && shares_kv[k + 1]) continue;
         int32_t nb = ceil_div(kv_len[k], BN);
-        int32_t nqb = ceil_div(q_len[k], BM);
         for (int32_t b = 0; b < nb; ++b) {
-            int64_t i0 = (int64_t)b * BN - q_begin[k];
-            if (i0 < 0) i0 = 0;
-            int32_t m0 = (int32_t)(i0 / BM);
+            int32_t m0 = 0, cost = 0;
+            for (int32_t s = k; s >= k - (shares_kv[k] ? 1 : 0); --s) {
+                if ((int64_t)b * BN >= kv_len[s]) continue;
+                int64_t i0 = (int64_t)b * BN - q_begin[s];
+                if (i0 < 0) i0 = 0;
+                if (s == k) m0 = (int32_t)(i0 / BM);
+                cost += ceil_div(q_len[s], BM) - (int32_t)(i0 / BM);
+            }
             if (items) {
                 items[4 * n + 0] = k;
                 items[4 * n + 1] = b;
                 items[4 * n + 2] = m0;
-                items[4 * n + 3] = nqb - m0;
+                items[4 * n + 3] = cost;
             }
             ++n;
         }
@@ -173,9 +210,10 @@ int32_t oracle_dkv_items(int32_t K, const int32_t *q_begin, const int32_t *q_len
 /* Floating part                                                       */
 /* ------------------------------------------------------------------ */
 
-/* Shapes shared by the three functions below.
- *   Q, dO : [Tq, Hq, d] float, packed; sequence k owns rows cu_q[k]..cu_q[k+1]
- *   K, V  : [Tk, Hkv, d] float, packed; sequence k owns rows cu_k[k]..cu_k[k+1],
+/* Shapes shared by the three functions below ("sequence k" = segment k of
+ * oracle_ranges).
+ *   Q, dO : [Tq, Hq, d] float, packed; segment k owns rows cu_q[k]..cu_q[k]+q_len[k]-1
+ *   K, V  : [Tk, Hkv, d] float, packed; segment k reads rows cu_k[k]..cu_k[k]+kv_len[k]-1,
  *           which are key positions 0..kv_len[k]-1
  * A work entry t names (seq[t], head[t], idx[t]).  Entries are independent and
  * are spread over the host cores. */
@@ -286,7 +324,9 @@ void oracle_bwd_dq_rows(const float *Q, const float *Kt, const float *V, const f
  *   dV_j  = sum P_ij dO_i,   dK_j = scale * sum dS_ij q_i
  * LSEfull and Dfull are [Hq, Tq] doubles from the two functions above; only
  * the (head, row) cells the listed columns can see are read.
- * For a shard these are this rank's partial sums over its own query rows. */
+ * For a shard these are this rank's partial sums over its own query rows.  When two
+ * segments share a key/value prefix, the gradient of a key row is the sum of the
+ * columns of both (the caller adds them). */
 void oracle_bwd_dkv_cols(const float *Q, const float *Kt, const float *V, const float *dO,
                          const double *LSEfull, const double *Dfull, int64_t Tq,
                          int32_t Hq, int32_t Hkv, int32_t d, double scale,

@@ -77,3 +77,30 @@ def test_driver_reports_every_rank(capsys):
     assert sum(r["tokens"] for r in rep["plain_cp"]["ranks"]) == rep["tokens"]
     assert max(r["tokens"] for r in rep["dacp"]["ranks"]) <= rep["bucket_size"]
     assert rep["dacp"]["max_ms"] >= rep["dacp"]["min_ms"] > 0
+
+
+def test_gds_driver_runs_a_whole_iteration(capsys):
+    from paper_2505_19609_amd import gds_run
+    rc = gds_run.main(["--dataset", "wikipedia", "--model", "qwen2.5-0.5b", "--cp", "2", "--dp", "2",
+                       "--batch-size", "12", "--bucket", "2048", "--reps", "1", "--seed", "1"])
+    assert rc == 0
+    rep = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    assert len(rep["dp_ranks"]) == 2
+    assert sum(r["num_seqs"] for r in rep["dp_ranks"]) == rep["num_seqs"] == 24
+    for r in rep["dp_ranks"]:
+        assert sum(m["tokens"] for m in r["micro_batches"]) == r["tokens"]
+        assert all(m["tokens"] <= 2 * 2048 for m in r["micro_batches"])   # C*N per micro-batch
+        assert abs(sum(m["max_ms"] for m in r["micro_batches"]) - r["sum_max_ms"]) < 1e-2
+    assert rep["iteration_ms"] == max(r["sum_max_ms"] for r in rep["dp_ranks"])
+
+
+def test_calibration_fit(capsys):
+    from paper_2505_19609_amd import calibrate
+    rc = calibrate.main(["--model", "qwen2.5-7b", "--cp", "4", "--lengths", "512", "2048", "8192", "--reps", "2"])
+    assert rc == 0
+    rep = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    assert len(rep["rows"]) == 3 and rep["alpha_ms_per_flop"] > 0
+    ms = [r["whole_ms"] for r in rep["rows"]]
+    assert ms[0] < ms[1] < ms[2]
+    # the last contiguous slice sees (2N-1) times the pairs of the first one
+    assert rep["rows"][2]["slice_last_ms"] > rep["rows"][2]["slice_first_ms"]
