@@ -6,20 +6,23 @@
  * holds every local sequence assigned to it whole (P_kj = 1) and a 1/N slice
  * of every distributed sequence (D_k = 1; Eq. 8 charges S_k/N of its tokens to
  * each rank).  The caller states it exactly that way: a list of full sequence
- * lengths S[K], and per sequence a shard degree (1 = local, N = distributed)
- * and the shard index this GPU holds.  Sequences are packed without padding
- * (App. B.1) and never attend to one another.  A shard is the contiguous query
- * range [floor(r*S/N), floor((r+1)*S/N)) attending to the gathered key/value
- * prefix [0, q_end) at its true positions (the paper leaves the cut open; it
- * only fixes the S/N token count).
+ * lengths S[K], and per sequence a shard degree (1 = local, N = distributed),
+ * the shard index this GPU holds and, optionally, how the sequence is cut.
+ * Sequences are packed without padding (App. B.1) and never attend to one
+ * another.  By default a shard is the contiguous query range
+ * [floor(r*S/N), floor((r+1)*S/N)) attending to the gathered key/value prefix
+ * [0, q_end) at its true positions (the paper leaves the cut open; it only
+ * fixes the S/N token count); SKRULL_CUT_TWO_CHUNKS below is the alternative.
  *
  * All tensors are caller-owned DEVICE memory, contiguous, 16-byte aligned,
  * token-major with head_dim innermost:
  *   Q, O, dQ, dO : bf16 [total_q, num_q_heads, head_dim]
  *   K, V, dK, dV : bf16 [total_k, num_kv_heads, head_dim]
  *   LSE          : fp32 [num_q_heads, total_q]   (natural log, scale included)
- * Sequence k owns query rows cu_q[k]..cu_q[k+1]-1 and key/value rows
- * cu_k[k]..cu_k[k+1]-1; the latter are key positions 0..kv_len[k]-1.
+ * Sequences follow one another in both packings in the caller's order: sequence k
+ * owns the next q_len rows of Q/O/dQ/dO (its slice, or its two chunks one after
+ * the other) and the next kv_len rows of K/V/dK/dV, which are key positions
+ * 0..kv_len-1 of its prefix.
  * Query head h reads key/value head h / (num_q_heads / num_kv_heads).
  *
  * Every function returns 0 (SKRULL_OK) or a negative code; nothing throws or
@@ -58,7 +61,25 @@ typedef struct {
     float          softmax_scale; /* finite, > 0; multiplies Q.K^T inside the kernels          */
     int32_t        block_m;       /* query rows per work item: 64, 128 or 256; 0 = 256          */
     int32_t        block_n;       /* key rows per dK/dV work item: 64, 128 or 256; 0 = 128      */
+    const int32_t *shard_cut;     /* [K] HOST or NULL (= all SKRULL_CUT_CONTIGUOUS)             */
 } skrull_attn_problem_t;
+
+/*
+ * How a distributed sequence is cut (the paper fixes only the S_k/N tokens per rank,
+ * Eq. 8, and charges every rank FLOPs/N, Eq. 4):
+ *  SKRULL_CUT_CONTIGUOUS  the slice [floor(r*S/N), floor((r+1)*S/N)); under the causal
+ *                         mask rank r does (2r+1)/N^2 of the work.
+ *  SKRULL_CUT_TWO_CHUNKS  the sequence is cut into 2N chunks [floor(i*S/2N),
+ *                         floor((i+1)*S/2N)) and rank r holds chunks r and 2N-1-r, so
+ *                         every rank does 1/N of the work up to rounding, which is what
+ *                         Eq. 4 assumes.  Needs 2N <= S_k.  The rank's rows of
+ *                         Q/O/dQ/dO/LSE are chunk r's followed by chunk 2N-1-r's; its
+ *                         K/V/dK/dV rows are the prefix [0, end of chunk 2N-1-r).
+ * Inside the library such a sequence is two consecutive query SEGMENTS that share one
+ * key/value prefix; a contiguous slice or a local sequence is one segment.
+ */
+#define SKRULL_CUT_CONTIGUOUS 0
+#define SKRULL_CUT_TWO_CHUNKS 1
 
 typedef struct {
     int32_t num_seqs, num_q_heads, num_kv_heads, head_dim;
@@ -71,17 +92,22 @@ typedef struct {
     int64_t useful_flops_fwd;     /*  4 * pairs * head_dim * Hq                                */
     int64_t useful_flops_bwd;     /* 10 * pairs * head_dim * Hq                                */
     int64_t bwd_workspace_bytes;  /* device scratch skrull_attn_bwd needs (>= 0)               */
+    int32_t num_segments;         /* query segments: K + number of two-chunk sequences         */
+    int32_t reserved;
 } skrull_attn_plan_info_t;
 
-/* Arrays a plan holds on the device, for skrull_attn_plan_export. */
+/* Arrays a plan holds on the device, for skrull_attn_plan_export.  They are per
+ * query segment (NS = num_segments entries; NS = K when no sequence is cut in two
+ * chunks, and then a segment is a sequence). */
 enum {
-    SKRULL_ARRAY_CU_Q      = 0,   /* int32 [K+1]  exclusive prefix sums of q_len               */
-    SKRULL_ARRAY_CU_K      = 1,   /* int32 [K+1]  exclusive prefix sums of kv_len              */
-    SKRULL_ARRAY_Q_BEGIN   = 2,   /* int32 [K]    global position of the first local query     */
-    SKRULL_ARRAY_Q_LEN     = 3,   /* int32 [K]                                                 */
-    SKRULL_ARRAY_KV_LEN    = 4,   /* int32 [K]                                                 */
-    SKRULL_ARRAY_FWD_ITEMS = 5,   /* int32 [n_fwd_items][4] = {seq, q_block, q_row, n_kv}      */
-    SKRULL_ARRAY_DKV_ITEMS = 6    /* int32 [n_dkv_items][4] = {seq, kv_block, m0, n_q}         */
+    SKRULL_ARRAY_CU_Q      = 0,   /* int32 [NS+1] first packed Q row of the segment; total     */
+    SKRULL_ARRAY_CU_K      = 1,   /* int32 [NS+1] first packed K/V row of its prefix; total    */
+    SKRULL_ARRAY_Q_BEGIN   = 2,   /* int32 [NS]   global position of the first local query     */
+    SKRULL_ARRAY_Q_LEN     = 3,   /* int32 [NS]                                                */
+    SKRULL_ARRAY_KV_LEN    = 4,   /* int32 [NS]   q_begin + q_len: the keys the segment sees   */
+    SKRULL_ARRAY_FWD_ITEMS = 5,   /* int32 [n_fwd_items][4] = {segment, q_block, q_row, n_kv}  */
+    SKRULL_ARRAY_DKV_ITEMS = 6,   /* int32 [n_dkv_items][4] = {segment, kv_block, m0, n_q}     */
+    SKRULL_ARRAY_SHARES_KV = 7    /* int32 [NS]   1 = late chunk: shares the prefix of NS-1    */
 };
 
 /*
@@ -91,11 +117,13 @@ enum {
  * argmin(L) and Alg. 2's FLOPs bin-packing -- to compute units: items are
  * stably sorted by descending quadratic cost and dispatched in that order).
  *
- * Forward/dQ list: one item per (sequence, block of block_m query rows), cost
+ * Forward/dQ list: one item per (segment, block of block_m query rows), cost
  * n_kv = ceil((q_begin + last_row + 1) / block_n).  dK/dV list: one item per
- * (sequence, block of block_n key rows), m0 = first query block that can see
- * it, cost n_q = number of query blocks that do.  Ties keep (sequence, block)
- * ascending order, so the layout is a pure function of the inputs.
+ * (key/value prefix, block of block_n key rows), named by the last segment that
+ * reads the prefix; m0 = that segment's first query block that can see the
+ * block, cost n_q = number of query blocks that do (of both segments when the
+ * prefix is shared).  Ties keep (segment, block) ascending order, so the layout
+ * is a pure function of the inputs.
  *
  * p and the three arrays it points to are HOST memory, read before return.
  * `hip_stream` (a hipStream_t, may be NULL for the default stream) carries the
@@ -104,7 +132,8 @@ enum {
  * skrull_attn_plan_destroy.  A plan is immutable and may be reused by any
  * number of fwd/bwd calls on any stream of the same device.
  * SKRULL_EINVAL: null pointer, K < 1, S_k < 1, degree < 1, index outside
- * [0, degree), degree > S_k, Hq % Hkv != 0, head_dim not 64/128, a block size
+ * [0, degree), more chunks than tokens (degree > S_k, or 2*degree > S_k for a
+ * two-chunk cut), a cut other than the two above, Hq % Hkv != 0, head_dim not 64/128, a block size
  * other than 0/64/128/256, scale not finite/positive, a total of 2^31 rows or
  * more, or more than 2^20 work items in either list.
  */

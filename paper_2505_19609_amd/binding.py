@@ -13,7 +13,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libskrull_attn.so")
 
 SKRULL_OK, SKRULL_EINVAL, SKRULL_ENOMEM, SKRULL_EHIP, SKRULL_EUNSUPPORTED, SKRULL_ESCHED = 0, -1, -2, -3, -4, -5
-ARRAY_CU_Q, ARRAY_CU_K, ARRAY_Q_BEGIN, ARRAY_Q_LEN, ARRAY_KV_LEN, ARRAY_FWD_ITEMS, ARRAY_DKV_ITEMS = range(7)
+(ARRAY_CU_Q, ARRAY_CU_K, ARRAY_Q_BEGIN, ARRAY_Q_LEN, ARRAY_KV_LEN, ARRAY_FWD_ITEMS, ARRAY_DKV_ITEMS,
+ ARRAY_SHARES_KV) = range(8)
+CUT_CONTIGUOUS, CUT_TWO_CHUNKS = 0, 1
 
 EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
                     "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_plan_destroy",
@@ -32,7 +34,8 @@ class Problem(ctypes.Structure):
                 ("head_dim", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float),
                 ("block_m", ctypes.c_int32),
-                ("block_n", ctypes.c_int32)]
+                ("block_n", ctypes.c_int32),
+                ("shard_cut", ctypes.POINTER(ctypes.c_int32))]
 
 
 class PlanInfo(ctypes.Structure):
@@ -42,7 +45,8 @@ class PlanInfo(ctypes.Structure):
                 ("total_q", ctypes.c_int32), ("total_k", ctypes.c_int32),
                 ("n_fwd_items", ctypes.c_int32), ("n_dkv_items", ctypes.c_int32),
                 ("attended_pairs", ctypes.c_int64), ("useful_flops_fwd", ctypes.c_int64),
-                ("useful_flops_bwd", ctypes.c_int64), ("bwd_workspace_bytes", ctypes.c_int64)]
+                ("useful_flops_bwd", ctypes.c_int64), ("bwd_workspace_bytes", ctypes.c_int64),
+                ("num_segments", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class FlopsModel(ctypes.Structure):
@@ -147,16 +151,19 @@ class Plan:
 
 
 def skrull_attn_plan(seq_len, shard_degree, shard_index, num_q_heads, num_kv_heads, head_dim,
-                     softmax_scale, block_m=0, block_n=0, stream=None, raw_stream=None) -> Plan:
+                     softmax_scale, block_m=0, block_n=0, stream=None, raw_stream=None,
+                     shard_cut=None) -> Plan:
     S = np.ascontiguousarray(seq_len, dtype=np.int32)
     N = np.ascontiguousarray(shard_degree, dtype=np.int32)
     R = np.ascontiguousarray(shard_index, dtype=np.int32)
-    if not (S.shape == N.shape == R.shape and S.ndim == 1):
-        raise SkrullError(SKRULL_EINVAL, "seq_len / shard_degree / shard_index must be 1-D and equally long")
+    Z = None if shard_cut is None else np.ascontiguousarray(shard_cut, dtype=np.int32)
+    if not (S.shape == N.shape == R.shape and S.ndim == 1 and (Z is None or Z.shape == S.shape)):
+        raise SkrullError(SKRULL_EINVAL, "seq_len / shard_degree / shard_index / shard_cut must be 1-D and equally long")
     i32p = ctypes.POINTER(ctypes.c_int32)
     prob = Problem(int(S.shape[0]), S.ctypes.data_as(i32p), N.ctypes.data_as(i32p),
                    R.ctypes.data_as(i32p), num_q_heads, num_kv_heads, head_dim,
-                   float(softmax_scale), block_m, block_n)
+                   float(softmax_scale), block_m, block_n,
+                   None if Z is None else Z.ctypes.data_as(i32p))
     handle = ctypes.c_void_p()
     st = ctypes.c_void_p(raw_stream) if raw_stream is not None else _stream_ptr(stream)
     _check(lib().skrull_attn_plan(ctypes.byref(prob), st, ctypes.byref(handle)))
@@ -172,9 +179,9 @@ def skrull_attn_plan_info(plan: Plan) -> PlanInfo:
 
 
 def skrull_attn_plan_export(plan: Plan, which: int) -> np.ndarray:
-    K = plan.info.num_seqs
+    K = plan.info.num_segments
     shape = {ARRAY_CU_Q: (K + 1,), ARRAY_CU_K: (K + 1,), ARRAY_Q_BEGIN: (K,), ARRAY_Q_LEN: (K,),
-             ARRAY_KV_LEN: (K,), ARRAY_FWD_ITEMS: (plan.info.n_fwd_items, 4),
+             ARRAY_KV_LEN: (K,), ARRAY_SHARES_KV: (K,), ARRAY_FWD_ITEMS: (plan.info.n_fwd_items, 4),
              ARRAY_DKV_ITEMS: (plan.info.n_dkv_items, 4)}[which]
     out = np.zeros(shape, np.int32)
     _check(lib().skrull_attn_plan_export(plan.handle, which, out.ctypes.data_as(ctypes.c_void_p),

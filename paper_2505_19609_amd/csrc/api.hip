@@ -74,30 +74,35 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         return SKRULL_EINVAL;
     // Entry checks that need no arithmetic are done here so that they work
     // without a device; the kernel repeats them next to the range computation.
+    int64_t n_seg = 0;  // query segments: a two-chunk cut contributes two
     for (int32_t k = 0; k < K; ++k) {
         const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
-        if (s < 1 || n < 1 || r < 0 || r >= n || n > s) return SKRULL_EINVAL;
+        const int32_t z = p->shard_cut ? p->shard_cut[k] : SKRULL_CUT_CONTIGUOUS;
+        if (z != SKRULL_CUT_CONTIGUOUS && z != SKRULL_CUT_TWO_CHUNKS) return SKRULL_EINVAL;
+        if (s < 1 || n < 1 || r < 0 || r >= n || (int64_t)n * (1 + z) > s) return SKRULL_EINVAL;
+        n_seg += 1 + z;
     }
+    if (n_seg > INT32_MAX / 2) return SKRULL_EINVAL;
     int dev = 0;
     int rc = check_device(&dev);
     if (rc != SKRULL_OK) return rc;
 
     hipStream_t st = (hipStream_t)hip_stream;
     skrull_attn_plan_t *plan = nullptr;
-    int32_t *tmp = nullptr, *scratch = nullptr;
+    int32_t *tmp = nullptr, *scratch = nullptr, *fwd_off = nullptr, *dkv_off = nullptr;
     PlanTotals *totals_d = nullptr;
     PlanTotals totals;
-    // tmp: S, N, R [K each], fwd_off, dkv_off [K+1 each]
-    const int64_t kpad = align4(K + 1);
-    const int64_t desc_ints = 5 * kpad;
+    // tmp: S, N, R, cut [K each], fwd_off, dkv_off [n_seg+1 each]
+    const int64_t kin = align4(K), kpad = align4(n_seg + 1);
+    const int64_t desc_ints = 6 * kpad;
 
     plan = new (std::nothrow) skrull_attn_plan_t();
     if (!plan) return SKRULL_ENOMEM;
     memset(plan, 0, sizeof *plan);
-    plan->K = K; plan->Hq = p->num_q_heads; plan->Hkv = p->num_kv_heads; plan->d = p->head_dim;
+    plan->K = K; plan->NS = (int32_t)n_seg; plan->Hq = p->num_q_heads; plan->Hkv = p->num_kv_heads; plan->d = p->head_dim;
     plan->BM = BM; plan->BN = BN; plan->scale = p->softmax_scale; plan->device = dev;
 
-    HIP_TRY(hipMalloc((void **)&tmp, (size_t)(5 * kpad) * sizeof(int32_t)));
+    HIP_TRY(hipMalloc((void **)&tmp, (size_t)(4 * kin + 2 * kpad) * sizeof(int32_t)));
     HIP_TRY(hipMalloc((void **)&totals_d, sizeof(PlanTotals)));
     HIP_TRY(hipMalloc((void **)&plan->pool, (size_t)desc_ints * sizeof(int32_t)));
     plan->cu_q = plan->pool;
@@ -105,17 +110,26 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     plan->q_begin = plan->pool + 2 * kpad;
     plan->q_len = plan->pool + 3 * kpad;
     plan->kv_len = plan->pool + 4 * kpad;
+    plan->shares_kv = plan->pool + 5 * kpad;
     HIP_TRY(hipMemcpyAsync(tmp, p->seq_len, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(tmp + kpad, p->shard_degree, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(tmp + 2 * kpad, p->shard_index, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(launch_plan_ranges(tmp, tmp + kpad, tmp + 2 * kpad, K, BM, BN,
+    HIP_TRY(hipMemcpyAsync(tmp + kin, p->shard_degree, (size_t)K * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(tmp + 2 * kin, p->shard_index, (size_t)K * 4, hipMemcpyHostToDevice, st));
+    if (p->shard_cut) {
+        HIP_TRY(hipMemcpyAsync(tmp + 3 * kin, p->shard_cut, (size_t)K * 4, hipMemcpyHostToDevice, st));
+    } else {
+        HIP_TRY(hipMemsetAsync(tmp + 3 * kin, 0, (size_t)K * 4, st));
+    }
+    fwd_off = tmp + 4 * kin;
+    dkv_off = fwd_off + kpad;
+    HIP_TRY(launch_plan_ranges(tmp, tmp + kin, tmp + 2 * kin, tmp + 3 * kin, K, BM, BN,
                                INT32_MAX / (p->num_q_heads * p->head_dim),
                                INT32_MAX / (p->num_kv_heads * p->head_dim), plan->q_begin,
-                               plan->q_len, plan->kv_len, plan->cu_q, plan->cu_k, tmp + 3 * kpad,
-                               tmp + 4 * kpad, totals_d, st));
+                               plan->q_len, plan->kv_len, plan->cu_q, plan->cu_k, plan->shares_kv,
+                               fwd_off, dkv_off, totals_d, st));
     HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (totals.bad_entry != 0 || totals.total_q > INT32_MAX || totals.total_k > INT32_MAX ||
+    if (totals.bad_entry != 0 || totals.n_seg != plan->NS || totals.total_q > INT32_MAX ||
+        totals.total_k > INT32_MAX ||
         totals.n_fwd > kMaxItems || totals.n_dkv > kMaxItems) {
         snprintf(g_err, sizeof g_err, "micro-batch too large or invalid entry %d", totals.bad_entry - 1);
         rc = SKRULL_EINVAL;
@@ -131,7 +145,7 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         HIP_TRY(hipMalloc((void **)&plan->fwd_items, item_bytes));
         plan->dkv_items = plan->fwd_items + 4 * (int64_t)plan->n_fwd;
         HIP_TRY(hipMalloc((void **)&scratch, item_bytes));
-        HIP_TRY(launch_plan_items(plan, tmp + 3 * kpad, tmp + 4 * kpad, scratch,
+        HIP_TRY(launch_plan_items(plan, fwd_off, dkv_off, scratch,
                                   scratch + 4 * (int64_t)plan->n_fwd, st));
         HIP_TRY(hipStreamSynchronize(st));
     }
@@ -169,6 +183,8 @@ int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_
     info->useful_flops_fwd = 4 * plan->pairs * plan->d * plan->Hq;
     info->useful_flops_bwd = 10 * plan->pairs * plan->d * plan->Hq;
     info->bwd_workspace_bytes = (((int64_t)plan->Hq * plan->total_q * 8) + 255) & ~(int64_t)255;
+    info->num_segments = plan->NS;
+    info->reserved = 0;
     return SKRULL_OK;
 }
 
@@ -178,11 +194,12 @@ int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst
     const int32_t *src = nullptr;
     size_t n = 0;
     switch (which) {
-    case SKRULL_ARRAY_CU_Q: src = plan->cu_q; n = (size_t)plan->K + 1; break;
-    case SKRULL_ARRAY_CU_K: src = plan->cu_k; n = (size_t)plan->K + 1; break;
-    case SKRULL_ARRAY_Q_BEGIN: src = plan->q_begin; n = (size_t)plan->K; break;
-    case SKRULL_ARRAY_Q_LEN: src = plan->q_len; n = (size_t)plan->K; break;
-    case SKRULL_ARRAY_KV_LEN: src = plan->kv_len; n = (size_t)plan->K; break;
+    case SKRULL_ARRAY_CU_Q: src = plan->cu_q; n = (size_t)plan->NS + 1; break;
+    case SKRULL_ARRAY_CU_K: src = plan->cu_k; n = (size_t)plan->NS + 1; break;
+    case SKRULL_ARRAY_Q_BEGIN: src = plan->q_begin; n = (size_t)plan->NS; break;
+    case SKRULL_ARRAY_Q_LEN: src = plan->q_len; n = (size_t)plan->NS; break;
+    case SKRULL_ARRAY_KV_LEN: src = plan->kv_len; n = (size_t)plan->NS; break;
+    case SKRULL_ARRAY_SHARES_KV: src = plan->shares_kv; n = (size_t)plan->NS; break;
     case SKRULL_ARRAY_FWD_ITEMS: src = plan->fwd_items; n = (size_t)plan->n_fwd * 4; break;
     case SKRULL_ARRAY_DKV_ITEMS: src = plan->dkv_items; n = (size_t)plan->n_dkv * 4; break;
     default: return SKRULL_EINVAL;

@@ -72,7 +72,7 @@ struct BwdParams {
     const float *lse, *delta, *lse2;
     uint16_t *dq, *dk, *dv;
     const int4 *fwd_items, *dkv_items;
-    const int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len;
+    const int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len, *shares_kv;
     int32_t Hq, Hkv, total_q, BM, BN;
     float scale, scale_log2;
 };
@@ -323,9 +323,27 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
         for (int ks = 0; ks < KS; ++ks) bf[ks] = as_bf16x8(*(const uint4 *)(src + off + 16 * ks));
     }
 
-    const int i_first = (max(0, kv0 - qb) / QT) * QT;  // first query tile that can see key kv0
-    const int n_qt = (ql - i_first + QT - 1) / QT;
+    // Query tiles that can see key kv0, numbered 0 .. n_qt-1 in position order: those of
+    // the early chunk (segment seq-1, when this prefix is shared by two chunks and the
+    // pass starts inside the early chunk's own prefix) and then those of segment seq.
+    const int i_first = (max(0, kv0 - qb) / QT) * QT;
+    const int n_qt_own = (ql - i_first + QT - 1) / QT;
+    int qb_e = 0, ql_e = 0, qbase_e = 0, i_first_e = 0, n_qt_e = 0;
+    if (prm.shares_kv[seq] && kv0 < prm.kv_len[seq - 1]) {
+        qb_e = prm.q_begin[seq - 1];
+        ql_e = prm.q_len[seq - 1];
+        qbase_e = prm.cu_q[seq - 1];
+        i_first_e = (max(0, kv0 - qb_e) / QT) * QT;
+        n_qt_e = (ql_e - i_first_e + QT - 1) / QT;
+    }
+    const int n_qt = n_qt_e + n_qt_own;
     const int n_iter = n_qt * g;  // (head, query tile) pairs
+    // tile t -> first global position of its segment, rows of the segment, first row of the tile
+    auto tile_qb = [&](int t) __attribute__((always_inline)) { return t < n_qt_e ? qb_e : qb; };
+    auto tile_ql = [&](int t) __attribute__((always_inline)) { return t < n_qt_e ? ql_e : ql; };
+    auto tile_i0 = [&](int t) __attribute__((always_inline)) {
+        return t < n_qt_e ? i_first_e + t * QT : i_first + (t - n_qt_e) * QT;
+    };
 
     f32x16 acc[TT];  // dV^T (role 0) or dK^T (role 1) of this lane's key
     zero_acc(acc);
@@ -333,15 +351,17 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
     // fetch of tile (head th of the group, query tile tq_idx) into ring slot `slot`
     auto fetch = [&](int th, int tq_idx, int slot) __attribute__((always_inline)) {
         const int head = c * g + th;
-        const int i0 = i_first + tq_idx * QT;
+        const int i0 = tile_i0(tq_idx);
+        const int rows = tile_ql(tq_idx);
+        const int first_row = tq_idx < n_qt_e ? qbase_e : qbase;
         const uint32_t base = ring0 + (uint32_t)slot * SLOT;
-        const size_t hoff = ((size_t)qbase * prm.Hq + head) * D;
-        // rows past the end of the sequence read as zero (and are masked)
-        ld.load(ld.rsrc(prm.q + hoff, ql), base, i0, wave);
-        ld.load(ld.rsrc(prm.d_o + hoff, ql), base + TB, i0, wave);
-        const size_t soff = (size_t)head * prm.total_q + qbase;
-        if (wave == 2) dma_b32(rsrc_words(prm.lse2 + soff, (uint32_t)ql * 4), base + 2 * TB, lane * 4, i0 * 4);
-        if (wave == 3) dma_b32(rsrc_words(prm.delta + soff, (uint32_t)ql * 4), base + 2 * TB + QT * 4, lane * 4, i0 * 4);
+        const size_t hoff = ((size_t)first_row * prm.Hq + head) * D;
+        // rows past the end of the segment read as zero (and are masked)
+        ld.load(ld.rsrc(prm.q + hoff, rows), base, i0, wave);
+        ld.load(ld.rsrc(prm.d_o + hoff, rows), base + TB, i0, wave);
+        const size_t soff = (size_t)head * prm.total_q + first_row;
+        if (wave == 2) dma_b32(rsrc_words(prm.lse2 + soff, (uint32_t)rows * 4), base + 2 * TB, lane * 4, i0 * 4);
+        if (wave == 3) dma_b32(rsrc_words(prm.delta + soff, (uint32_t)rows * 4), base + 2 * TB + QT * 4, lane * 4, i0 * 4);
     };
 
     fetch(0, n_qt - 1, 0);
@@ -363,15 +383,16 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             const int slot_next = slot == 2 ? 0 : slot + 1;
             if (T + 1 < n_iter) fetch(nh, nq, slot_next);
             const unsigned char *cur = lds_ring[slot];
-            const int i0 = i_first + cq * QT;  // first query row of the tile
+            const int i0 = tile_i0(cq);  // first query row of the tile inside its segment
+            const int qb_t = tile_qb(cq), ql_t = tile_ql(cq);
             // a tile is skipped when its last query still precedes this pair's first key
-            const bool act = T < n_iter && wave_active && qb + i0 + QT - 1 >= wj0;
+            const bool act = T < n_iter && wave_active && qb_t + i0 + QT - 1 >= wj0;
             if (act) {
                 const unsigned char *tq = cur, *tdo = cur + TB;
                 const float *t_lse = (const float *)(cur + 2 * TB);
                 unsigned char *px = lds_p[pw][T & 1][0];
                 // masked pairs: key past the query (causal) or query row past the end
-                const bool need_mask = (qb + i0 < wj0 + 31) || (i0 + QT > ql);
+                const bool need_mask = (qb_t + i0 < wj0 + 31) || (i0 + QT > ql_t);
                 f32x16 s[2];
                 bf16x8 fr[4];
                 // S of the first 32 rows; operand reads run three MFMAs ahead
@@ -473,7 +494,7 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
                             for (int e = 0; e < 4; ++e) {
                                 const int i = i0 + 32 * b + 8 * vb + 4 * h + e;
                                 const float pv = fast_exp2(__builtin_fmaf(s[b][4 * vb + e], cs, -lv[e]));
-                                s[b][4 * vb + e] = (my_j > qb + i || i >= ql) ? 0.0f : pv;
+                                s[b][4 * vb + e] = (my_j > qb_t + i || i >= ql_t) ? 0.0f : pv;
                             }
                         }
                     }
@@ -504,8 +525,7 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             const int slot_next = slot == 2 ? 0 : slot + 1, slot_prev = slot == 0 ? 2 : slot - 1;
             if (T + 1 < n_iter) fetch(nh, nq, slot_next);
             const unsigned char *cur = lds_ring[slot], *prv = lds_ring[slot_prev];
-            const int i0 = i_first + cq * QT;
-            const bool act = T < n_iter && wave_active && qb + i0 + QT - 1 >= wj0;
+            const bool act = T < n_iter && wave_active && tile_qb(cq) + tile_i0(cq) + QT - 1 >= wj0;
             const unsigned char *tdo = cur + TB;
             const float *t_nd = (const float *)(cur + 2 * TB) + QT;  // -D of this round's tile
             const unsigned char *pp = lds_p[pw][(T - 1) & 1][0];
@@ -656,7 +676,7 @@ hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     prm.dq = (uint16_t *)dq; prm.dk = (uint16_t *)dk; prm.dv = (uint16_t *)dv;
     prm.fwd_items = (const int4 *)p->fwd_items; prm.dkv_items = (const int4 *)p->dkv_items;
     prm.cu_q = p->cu_q; prm.cu_k = p->cu_k; prm.q_begin = p->q_begin; prm.q_len = p->q_len;
-    prm.kv_len = p->kv_len;
+    prm.kv_len = p->kv_len; prm.shares_kv = p->shares_kv;
     prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM; prm.BN = p->BN;
     prm.scale = p->scale; prm.scale_log2 = p->scale * kLog2e;
     if (p->d == 128) return launch_d<128>(p, prm, o, delta, st, ev);

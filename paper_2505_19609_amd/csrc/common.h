@@ -9,14 +9,14 @@
 
 // Device-resident descriptor + work lists of one micro-batch.
 struct skrull_attn_plan {
-    int32_t K, Hq, Hkv, d, BM, BN;
+    int32_t K, NS, Hq, Hkv, d, BM, BN;  // K sequences, NS >= K query segments
     float scale;
     int32_t total_q, total_k, n_fwd, n_dkv;
     int64_t pairs;
     int device;
     // one allocation; the pointers below index into it
     int32_t *pool;
-    int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len;  // [K+1],[K+1],[K],[K],[K]
+    int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len, *shares_kv;  // per segment: [NS+1] x2, [NS] x4
     int32_t *fwd_items, *dkv_items;                   // [n][4], sorted
 };
 
@@ -24,15 +24,16 @@ struct skrull_attn_plan {
 struct PlanTotals {
     int64_t total_q, total_k, n_fwd, n_dkv, pairs;
     int32_t bad_entry;   // index+1 of the first invalid sequence, 0 if none
-    int32_t pad;
+    int32_t n_seg;       // number of query segments
 };
 
 // plan.hip
-hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r, int32_t K,
-                              int32_t BM, int32_t BN, int32_t max_q_rows, int32_t max_k_rows,
-                              int32_t *q_begin, int32_t *q_len,
-                              int32_t *kv_len, int32_t *cu_q, int32_t *cu_k, int32_t *fwd_off,
-                              int32_t *dkv_off, PlanTotals *totals, hipStream_t st);
+hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r,
+                              const int32_t *cut, int32_t K, int32_t BM, int32_t BN,
+                              int32_t max_q_rows, int32_t max_k_rows, int32_t *q_begin,
+                              int32_t *q_len, int32_t *kv_len, int32_t *cu_q, int32_t *cu_k,
+                              int32_t *shares_kv, int32_t *fwd_off, int32_t *dkv_off,
+                              PlanTotals *totals, hipStream_t st);
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
                              const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
                              hipStream_t st);

@@ -2,10 +2,11 @@
 //
 // The micro-batch is stated the way the paper states it (Sec. 4.1, Eq. 1-8):
 // full lengths S[K] plus, per sequence, local (degree 1) or distributed over N
-// ranks with this GPU holding slice `index` (Eq. 8: S_k/N tokens per rank).
+// ranks with this GPU holding slice `index` (Eq. 8: S_k/N tokens per rank), cut
+// either as one contiguous slice or as two chunks that balance the causal work.
 // Three small kernels:
-//   1. plan_ranges : per-sequence query/KV ranges, the packed offsets
-//                    (exclusive scans), per-sequence work-item offsets, totals
+//   1. plan_ranges : per-segment query/KV ranges, the packed offsets
+//                    (exclusive scans), per-segment work-item offsets, totals
 //   2. plan_emit   : one thread per work item writes {seq, block, x, cost}
 //   3. plan_sort   : stable descending-cost order by rank counting, so the
 //                    hardware dispatcher, which hands out workgroups in grid
@@ -40,70 +41,95 @@ __device__ inline int64_t block_exclusive_scan(int64_t v, int64_t *lds, int64_t 
 
 __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// One thread per sequence.  A sequence cut the contiguous way is one query
+// segment; one cut the load-balanced way (chunks r and 2N-1-r of 2N) is two
+// consecutive segments, early chunk first, that share one key/value prefix (the
+// late chunk's).  All per-segment arrays are indexed by segment; fwd_off / dkv_off
+// are the work-item offsets (an early chunk owns no dK/dV items: its offset equals
+// its partner's).
 __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
     const int32_t *__restrict__ S, const int32_t *__restrict__ N, const int32_t *__restrict__ R,
-    int32_t K, int32_t BM, int32_t BN, int32_t max_q_rows, int32_t max_k_rows,
-    int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
+    const int32_t *__restrict__ Z, int32_t K, int32_t BM, int32_t BN, int32_t max_q_rows,
+    int32_t max_k_rows, int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
     int32_t *__restrict__ kv_len, int32_t *__restrict__ cu_q, int32_t *__restrict__ cu_k,
-    int32_t *__restrict__ fwd_off, int32_t *__restrict__ dkv_off, PlanTotals *__restrict__ totals)
+    int32_t *__restrict__ shares_kv, int32_t *__restrict__ fwd_off, int32_t *__restrict__ dkv_off,
+    PlanTotals *__restrict__ totals)
 {
     __shared__ int64_t lds[kScanThreads];
     __shared__ int32_t first_bad;
     const int t = threadIdx.x;
     if (t == 0) first_bad = 0x7fffffff;
     __syncthreads();
-    int64_t base_q = 0, base_k = 0, base_f = 0, base_d = 0, pairs = 0;
+    int64_t base_s = 0, base_q = 0, base_k = 0, base_f = 0, base_d = 0, pairs = 0;
     for (int32_t k0 = 0; k0 < K; k0 += kScanThreads) {
         const int32_t k = k0 + t;
-        int64_t ql = 0, kl = 0, nf = 0, nd = 0, qb = 0, pr = 0;
+        int64_t qb[2] = {0, 0}, ql[2] = {0, 0}, nf[2] = {0, 0};
+        int64_t nseg = 0, owned = 0, nd = 0, pr = 0;
         if (k < K) {
-            const int64_t s = S[k], n = N[k], r = R[k];
-            if (s < 1 || n < 1 || r < 0 || r >= n || n > s) {
+            const int64_t s = S[k], n = N[k], r = R[k], z = Z[k];
+            const int64_t chunks = n * (z ? 2 : 1);
+            if (s < 1 || n < 1 || r < 0 || r >= n || (z != 0 && z != 1) || chunks > s) {
                 atomicMin(&first_bad, k);
             } else {
-                qb = (r * s) / n;
-                kl = ((r + 1) * s) / n;
-                ql = kl - qb;
+                nseg = z + 1;
+                const int64_t idx[2] = {r, 2 * n - 1 - r};
+                for (int part = 0; part < nseg; ++part) {
+                    const int64_t b = (idx[part] * s) / chunks, e = ((idx[part] + 1) * s) / chunks;
+                    qb[part] = b;
+                    ql[part] = e - b;
+                    nf[part] = ceil_div64(e - b, BM);
+                    pr += (e * (e + 1) - b * (b + 1)) / 2;
+                    owned = e;  // the late chunk's prefix covers the early one's
+                }
                 // one sequence of one tensor must span fewer than 2^31 elements
                 // (the kernels address inside a sequence with 32-bit offsets)
-                if (ql > max_q_rows || kl > max_k_rows) atomicMin(&first_bad, k);
-                nf = ceil_div64(ql, BM);
-                nd = ceil_div64(kl, BN);
-                pr = (kl * (kl + 1) - qb * (qb + 1)) / 2;
+                if (ql[0] + ql[1] > max_q_rows || owned > max_k_rows) atomicMin(&first_bad, k);
+                nd = ceil_div64(owned, BN);
             }
-            q_begin[k] = (int32_t)qb;
-            q_len[k] = (int32_t)ql;
-            kv_len[k] = (int32_t)kl;
         }
         int64_t tot;
-        int64_t e = block_exclusive_scan(ql, lds, &tot);
-        if (k < K) cu_q[k] = (int32_t)(base_q + e);
+        const int64_t e_s = block_exclusive_scan(nseg, lds, &tot);
+        const int64_t seg0 = base_s + e_s;
+        base_s += tot;
+        const int64_t e_q = block_exclusive_scan(ql[0] + ql[1], lds, &tot);
+        const int64_t row0 = base_q + e_q;
         base_q += tot;
-        e = block_exclusive_scan(kl, lds, &tot);
-        if (k < K) cu_k[k] = (int32_t)(base_k + e);
+        const int64_t e_k = block_exclusive_scan(owned, lds, &tot);
+        const int64_t krow0 = base_k + e_k;
         base_k += tot;
-        e = block_exclusive_scan(nf, lds, &tot);
-        if (k < K) fwd_off[k] = (int32_t)(base_f + e);
+        const int64_t e_f = block_exclusive_scan(nf[0] + nf[1], lds, &tot);
+        const int64_t f0 = base_f + e_f;
         base_f += tot;
-        e = block_exclusive_scan(nd, lds, &tot);
-        if (k < K) dkv_off[k] = (int32_t)(base_d + e);
+        const int64_t e_d = block_exclusive_scan(nd, lds, &tot);
+        const int64_t d0 = base_d + e_d;
         base_d += tot;
         block_exclusive_scan(pr, lds, &tot);
         pairs += tot;
+        for (int part = 0; part < nseg; ++part) {
+            const int64_t sg = seg0 + part;
+            q_begin[sg] = (int32_t)qb[part];
+            q_len[sg] = (int32_t)ql[part];
+            kv_len[sg] = (int32_t)(qb[part] + ql[part]);
+            cu_q[sg] = (int32_t)(row0 + (part ? ql[0] : 0));
+            cu_k[sg] = (int32_t)krow0;
+            shares_kv[sg] = part;
+            fwd_off[sg] = (int32_t)(f0 + (part ? nf[0] : 0));
+            dkv_off[sg] = (int32_t)d0;
+        }
     }
     __syncthreads();
     if (t == 0) {
-        cu_q[K] = (int32_t)base_q;
-        cu_k[K] = (int32_t)base_k;
-        fwd_off[K] = (int32_t)base_f;
-        dkv_off[K] = (int32_t)base_d;
+        cu_q[base_s] = (int32_t)base_q;
+        cu_k[base_s] = (int32_t)base_k;
+        fwd_off[base_s] = (int32_t)base_f;
+        dkv_off[base_s] = (int32_t)base_d;
         totals->total_q = base_q;
         totals->total_k = base_k;
         totals->n_fwd = base_f;
         totals->n_dkv = base_d;
         totals->pairs = pairs;
         totals->bad_entry = (first_bad == 0x7fffffff) ? 0 : first_bad + 1;
-        totals->pad = 0;
+        totals->n_seg = (int32_t)base_s;
     }
 }
 
@@ -121,7 +147,8 @@ __device__ inline int32_t owner_of(const int32_t *off, int32_t K, int32_t item)
 __global__ __launch_bounds__(256) void plan_emit_kernel(
     int32_t K, int32_t BM, int32_t BN, const int32_t *__restrict__ q_begin,
     const int32_t *__restrict__ q_len, const int32_t *__restrict__ kv_len,
-    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ fwd_off,
+    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ shares_kv,
+    const int32_t *__restrict__ fwd_off,
     const int32_t *__restrict__ dkv_off, int32_t n_fwd, int32_t n_dkv,
     int4 *__restrict__ fwd_items, int4 *__restrict__ dkv_items)
 {
@@ -136,13 +163,20 @@ __global__ __launch_bounds__(256) void plan_emit_kernel(
                                  (int32_t)ceil_div64((int64_t)q_begin[k] + row0 + rows, BN));
     }
     if (t < n_dkv) {
+        // equal offsets (an early chunk and its partner) resolve to the later segment,
+        // the one that owns the shared prefix
         const int32_t k = owner_of(dkv_off, K, t);
         const int32_t b = t - dkv_off[k];
         int64_t i0 = (int64_t)b * BN - q_begin[k];
         if (i0 < 0) i0 = 0;
         const int32_t m0 = (int32_t)(i0 / BM);
-        const int32_t nqb = (int32_t)ceil_div64(q_len[k], BM);
-        dkv_items[t] = make_int4(k, b, m0, nqb - m0);
+        int32_t cost = (int32_t)ceil_div64(q_len[k], BM) - m0;
+        if (shares_kv[k] && (int64_t)b * BN < kv_len[k - 1]) {  // query blocks of the early chunk
+            int64_t j0 = (int64_t)b * BN - q_begin[k - 1];
+            if (j0 < 0) j0 = 0;
+            cost += (int32_t)ceil_div64(q_len[k - 1], BM) - (int32_t)(j0 / BM);
+        }
+        dkv_items[t] = make_int4(k, b, m0, cost);
     }
 }
 
@@ -173,14 +207,16 @@ __global__ __launch_bounds__(256) void plan_sort_kernel(const int4 *__restrict__
 
 }  // namespace
 
-hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r, int32_t K,
-                              int32_t BM, int32_t BN, int32_t max_q_rows, int32_t max_k_rows,
-                              int32_t *q_begin, int32_t *q_len,
-                              int32_t *kv_len, int32_t *cu_q, int32_t *cu_k, int32_t *fwd_off,
-                              int32_t *dkv_off, PlanTotals *totals, hipStream_t st)
+hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r,
+                              const int32_t *cut, int32_t K, int32_t BM, int32_t BN,
+                              int32_t max_q_rows, int32_t max_k_rows, int32_t *q_begin,
+                              int32_t *q_len, int32_t *kv_len, int32_t *cu_q, int32_t *cu_k,
+                              int32_t *shares_kv, int32_t *fwd_off, int32_t *dkv_off,
+                              PlanTotals *totals, hipStream_t st)
 {
-    plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, K, BM, BN, max_q_rows, max_k_rows, q_begin, q_len, kv_len,
-                                                   cu_q, cu_k, fwd_off, dkv_off, totals);
+    plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, cut, K, BM, BN, max_q_rows, max_k_rows,
+                                                   q_begin, q_len, kv_len, cu_q, cu_k, shares_kv,
+                                                   fwd_off, dkv_off, totals);
     return hipGetLastError();
 }
 
@@ -190,7 +226,7 @@ hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off
 {
     const int32_t n = p->n_fwd > p->n_dkv ? p->n_fwd : p->n_dkv;
     plan_emit_kernel<<<(n + 255) / 256, 256, 0, st>>>(
-        p->K, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, fwd_off, dkv_off, p->n_fwd,
+        p->NS, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off, p->n_fwd,
         p->n_dkv, (int4 *)scratch_fwd, (int4 *)scratch_dkv);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -32,6 +32,7 @@ class Workload:
     q_prescale: float = 1.0
     note: str = ""
     extra: dict = field(default_factory=dict)
+    shard_cut: list | None = None   # per sequence: 0 = contiguous slice, 1 = chunks r and 2N-1-r of 2N
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:

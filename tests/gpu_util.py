@@ -15,7 +15,8 @@ def run_library(w, block_m=0, block_n=0, vals=None, backward=True, keep_device=F
     from paper_2505_19609_amd import workloads as W
 
     plan = B.skrull_attn_plan(w.seq_len, w.shard_degree, w.shard_index, w.num_q_heads,
-                              w.num_kv_heads, w.head_dim, w.softmax_scale, block_m, block_n)
+                              w.num_kv_heads, w.head_dim, w.softmax_scale, block_m, block_n,
+                              shard_cut=w.shard_cut)
     if vals is None:
         vals = W.make_values(w, plan.total_q, plan.total_k)
     dev = {n: to_dev(a) for n, a in vals.items()}

@@ -33,7 +33,7 @@ def _report(name, got, ref, tol):
 def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G):
     out = run_library(w, block_m, block_n)
     f = widen(out["vals"])
-    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
+    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index, w.shard_cut)
     O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
     dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
     _report("O", out["o"], O, TOL_O)
@@ -270,3 +270,74 @@ def test_shards_sum_to_unsharded_at_full_length():
         tol = (N + 1) * 0.5 * bf16_ulp(np.maximum(np.abs(f_), 1.0)) + 1e-2
         assert (err <= tol).all(), (name, err.max())
     full["plan"].destroy()
+
+
+# ---------------------------------------------------------------------------
+# load-balanced cut: chunks r and 2N-1-r of 2N, two query segments on one prefix
+# ---------------------------------------------------------------------------
+TWO_CHUNK = {
+    # name: (S, N, R, cut)
+    "one_pair": ([1000], [4], [1], [1]),
+    "first_and_last_rank": ([777, 777], [3, 3], [0, 2], [1, 1]),
+    "degree_one_is_the_whole_sequence": ([300], [1], [0], [1]),
+    "one_token_chunks": ([16, 130], [8, 1], [3, 0], [1, 0]),
+    "mixed_with_local_and_contiguous": ([700, 2049, 129, 1030, 64], [1, 4, 1, 2, 1], [0, 2, 0, 1, 0], [0, 1, 0, 0, 0]),
+    "ragged_everything": ([1001, 999, 515], [5, 7, 2], [4, 0, 1], [1, 1, 1]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(TWO_CHUNK))
+@pytest.mark.parametrize("heads,d", [((4, 2), 64), ((6, 2), 128)])
+def test_two_chunk_cut(oracle, name, heads, d):
+    S, N, R, Z = TWO_CHUNK[name]
+    w = W.Workload(name, S, N, R, heads[0], heads[1], d, d ** -0.5, 900 + len(S) + d, shard_cut=Z)
+    _exhaustive(oracle, w)
+
+
+@pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (128, 128)])
+def test_two_chunk_cut_block_sizes(oracle, bm, bn):
+    w = W.Workload("blocks2", [2100, 129, 1500], [3, 1, 2], [1, 0, 0], 4, 2, 128, 128 ** -0.5, 78,
+                   shard_cut=[1, 0, 1])
+    _exhaustive(oracle, w, bm, bn)
+
+
+def test_two_chunk_cut_scaled_down_twin(oracle):
+    """Structure of config 4 with the balanced cut, at a size the oracle covers."""
+    w = W.scaled_shard_twin(seq_len=8192, degree=8, index=2)
+    w.shard_cut = [1] + [0] * (len(w.seq_len) - 1)
+    _exhaustive(oracle, w)
+
+
+def test_two_chunk_cut_equals_its_two_slices_at_full_length():
+    """GPU vs GPU at config 4's length (131,072 tokens, 8 ranks): the two segments of a
+    two-chunk cut are the contiguous slices r and 2N-1-r of a 2N-way cut, which the
+    sampled oracle tests above cover.  O / LSE / dQ run the same work items on the same
+    rows, so they are equal bit for bit; dK / dV accumulate both chunks in fp32 and round
+    once, where the separate runs round each partial sum, so those agree to rounding."""
+    S, N, r, Hq, Hkv, d = 131072, 8, 2, 8, 2, 128
+    wz = W.Workload("two_chunks", [S], [N], [r], Hq, Hkv, d, d ** -0.5, 707, shard_cut=[1])
+    z = run_library(wz)
+    c = S // (2 * N)
+    la, lb = r * c, (2 * N - 1 - r) * c          # first rows of the two chunks
+    assert z["plan"].total_q == 2 * c and z["plan"].total_k == lb + c and z["plan"].num_segments == 2
+    dk = np.zeros_like(z["dk"], dtype=np.float64)
+    dv = np.zeros_like(z["dv"], dtype=np.float64)
+    for seg, (idx, first) in enumerate(((r, la), (2 * N - 1 - r, lb))):
+        rows = slice(seg * c, (seg + 1) * c)
+        vals = {"q": z["vals"]["q"][rows], "do": z["vals"]["do"][rows],
+                "k": z["vals"]["k"][:first + c], "v": z["vals"]["v"][:first + c]}
+        ws_ = W.Workload("slice", [S], [2 * N], [idx], Hq, Hkv, d, d ** -0.5, 707)
+        one = run_library(ws_, vals=vals)
+        assert np.array_equal(one["o"], z["o"][rows])
+        assert np.array_equal(one["lse"], z["lse"][:, rows])
+        assert np.array_equal(one["dq"], z["dq"][rows])
+        dk[:first + c] += one["dk"]
+        dv[:first + c] += one["dv"]
+        one["plan"].destroy()
+    for name, s_, f_ in (("dk", dk, z["dk"]), ("dv", dv, z["dv"])):
+        err = np.abs(s_ - f_)
+        tol = 1.5 * bf16_ulp(np.maximum(np.abs(f_), 1.0)) + 1e-2
+        assert (err <= tol).all(), (name, err.max())
+    # the pairs this rank attends are 1/N of the sequence's, up to rounding
+    assert abs(z["plan"].attended_pairs - S * (S + 1) // 2 // N) <= 2 * S
+    z["plan"].destroy()

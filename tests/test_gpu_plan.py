@@ -14,10 +14,11 @@ CASES = {
 }
 
 
-def _check(oracle, S, N, R, Hq, Hkv, d, bm, bn):
+def _check(oracle, S, N, R, Hq, Hkv, d, bm, bn, cut=None):
     from paper_2505_19609_amd import binding as B
-    plan = B.skrull_attn_plan(S, N, R, Hq, Hkv, d, 0.1, bm, bn)
-    desc = oracle.ranges(S, N, R)
+    plan = B.skrull_attn_plan(S, N, R, Hq, Hkv, d, 0.1, bm, bn, shard_cut=cut)
+    desc = oracle.ranges(S, N, R, cut)
+    assert plan.num_seqs == len(S) and plan.num_segments == desc["num_seqs"]
     BM, BN = plan.block_m, plan.block_n
     assert (BM, BN) == (bm or 256, bn or 128)
     assert plan.total_q == desc["total_q"] and plan.total_k == desc["total_k"]
@@ -26,7 +27,8 @@ def _check(oracle, S, N, R, Hq, Hkv, d, bm, bn):
     assert plan.useful_flops_bwd == 10 * plan.attended_pairs * d * Hq
     assert plan.bwd_workspace_bytes >= 4 * Hq * plan.total_q
     for which, name in ((B.ARRAY_CU_Q, "cu_q"), (B.ARRAY_CU_K, "cu_k"), (B.ARRAY_Q_BEGIN, "q_begin"),
-                        (B.ARRAY_Q_LEN, "q_len"), (B.ARRAY_KV_LEN, "kv_len")):
+                        (B.ARRAY_Q_LEN, "q_len"), (B.ARRAY_KV_LEN, "kv_len"),
+                        (B.ARRAY_SHARES_KV, "shares_kv")):
         assert np.array_equal(B.skrull_attn_plan_export(plan, which), desc[name]), name
     assert np.array_equal(B.skrull_attn_plan_export(plan, B.ARRAY_FWD_ITEMS), oracle.fwd_items(desc, BM, BN))
     assert np.array_equal(B.skrull_attn_plan_export(plan, B.ARRAY_DKV_ITEMS), oracle.dkv_items(desc, BM, BN))
@@ -48,6 +50,38 @@ def test_plan_matches_oracle_on_benchmark_configs(oracle, n, bm, bn):
 def test_plan_matches_oracle_on_edge_cases(oracle, name, bm, bn):
     S, N, R = CASES[name]
     _check(oracle, S, N, R, 4, 2, 64, bm, bn)
+
+
+TWO_CHUNK_CASES = {
+    "one_pair": ([1000], [4], [1], [1]),
+    "every_rank": ([4099] * 5, [5] * 5, [0, 1, 2, 3, 4], [1] * 5),
+    "one_token_chunks": ([16, 130, 6], [8, 1, 3], [3, 0, 2], [1, 0, 1]),
+    "mixed": ([700, 2049, 129, 1030, 64, 40000], [1, 4, 1, 2, 1, 8], [0, 2, 0, 1, 0, 5], [0, 1, 0, 0, 1, 1]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(TWO_CHUNK_CASES))
+@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 64), (128, 256), (256, 64)])
+def test_plan_matches_oracle_with_two_chunk_cuts(oracle, name, bm, bn):
+    S, N, R, Z = TWO_CHUNK_CASES[name]
+    _check(oracle, S, N, R, 4, 2, 64, bm, bn, cut=Z)
+
+
+def test_plan_many_two_chunk_sequences(oracle):
+    rng = np.random.Generator(np.random.PCG64(8))
+    S = rng.integers(2, 600, size=1500).tolist()
+    Z = rng.integers(0, 2, size=1500).tolist()
+    N = [int(min(s // (1 + z), n)) for s, z, n in zip(S, Z, rng.integers(1, 6, size=1500))]
+    R = [int(rng.integers(0, n)) for n in N]
+    _check(oracle, S, N, R, 8, 8, 128, 0, 0, cut=Z)
+
+
+def test_plan_rejects_bad_cuts():
+    from paper_2505_19609_amd import binding as B
+    for S, N, R, Z in (([7], [4], [0], [1]), ([70], [4], [0], [2]), ([70], [4], [0], [-1])):
+        with pytest.raises(B.SkrullError) as e:
+            B.skrull_attn_plan(S, N, R, 4, 2, 64, 0.1, shard_cut=Z)
+        assert e.value.code == B.SKRULL_EINVAL
 
 
 def test_plan_large_sequence_count(oracle):
