@@ -1,8 +1,9 @@
 """Offline profiling for the paper's latency model T_comp = alpha * FLOPs + beta
 (App. B.2): time this library's forward + backward on single whole sequences over a range
 of lengths and fit alpha, beta by least squares against the attention term of FLOPs(S),
-4*b*h*S^2 (the part of the layer this library computes).  Also times one contiguous
-1/N query slice per length, the unit DACP's FLOPs(S)/N stands for (Eq. 4).
+4*b*h*S^2 (the part of the layer this library computes).  Also times the 1/N share
+of each length that DACP's FLOPs(S)/N stands for (Eq. 4), for the first and the last rank under
+both cuts (contiguous slice, two balanced chunks).
 
     python -m paper_2505_19609_amd.calibrate --model qwen2.5-7b --cp 8
 """
@@ -38,10 +39,13 @@ def main(argv=None):
         whole, info = run_rank([L], [1], [0], (hq, hk), d, args.reps, L)
         row = {"S": L, "attn_flops_model": 4 * h * L * L, "whole_ms": round(whole, 4),
                "whole_useful_tflops": round(info["useful_flops"] / (whole * 1e-3) / 1e12, 1)}
-        if L >= args.cp:
+        if L >= 2 * args.cp:
             first, _ = run_rank([L], [args.cp], [0], (hq, hk), d, args.reps, L + 1)
             last, _ = run_rank([L], [args.cp], [args.cp - 1], (hq, hk), d, args.reps, L + 2)
-            row.update(slice_first_ms=round(first, 4), slice_last_ms=round(last, 4))
+            two0, _ = run_rank([L], [args.cp], [0], (hq, hk), d, args.reps, L + 3, cut=1)
+            two1, _ = run_rank([L], [args.cp], [args.cp - 1], (hq, hk), d, args.reps, L + 4, cut=1)
+            row.update(slice_first_ms=round(first, 4), slice_last_ms=round(last, 4),
+                       two_chunks_first_ms=round(two0, 4), two_chunks_last_ms=round(two1, 4))
         rows.append(row)
     x = np.array([r["attn_flops_model"] for r in rows], np.float64)
     y = np.array([r["whole_ms"] for r in rows], np.float64)

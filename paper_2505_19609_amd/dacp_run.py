@@ -34,13 +34,16 @@ def draw_micro_batch(dataset: str, bucket: int, cp: int, fill: float, seed: int)
     return W.table1_lengths(rng, dataset, budget=int(fill * bucket * cp), longest=bucket * cp)
 
 
-def run_rank(seq_len, degree, index, heads, head_dim, reps: int, seed: int):
-    """Forward + backward of one rank's micro-batch; returns (ms per fwd+bwd, plan totals)."""
+def run_rank(seq_len, degree, index, heads, head_dim, reps: int, seed: int, cut: int = 0):
+    """Forward + backward of one rank's micro-batch; returns (ms per fwd+bwd, plan totals).
+    `cut` is how distributed sequences are cut (0 contiguous slice, 1 two balanced chunks)."""
     import torch
     from . import binding as B
 
     hq, hkv = heads
-    plan = B.skrull_attn_plan(seq_len, degree, index, hq, hkv, head_dim, head_dim ** -0.5)
+    shard_cut = [cut if n > 1 else 0 for n in degree]
+    plan = B.skrull_attn_plan(seq_len, degree, index, hq, hkv, head_dim, head_dim ** -0.5,
+                              shard_cut=shard_cut)
     tq, tk = plan.total_q, plan.total_k
     gen = torch.Generator(device="cuda").manual_seed(seed)
 
@@ -69,7 +72,7 @@ def run_rank(seq_len, degree, index, heads, head_dim, reps: int, seed: int):
     return ms, info
 
 
-def run_schedule(S, ret, cp: int, heads, head_dim: int, reps: int, seed: int):
+def run_schedule(S, ret, cp: int, heads, head_dim: int, reps: int, seed: int, cut: int = 0):
     """Per-rank measurements of schedule `ret` (Alg. 1's output array)."""
     from . import binding as B
     ranks = []
@@ -79,7 +82,7 @@ def run_schedule(S, ret, cp: int, heads, head_dim: int, reps: int, seed: int):
             ranks.append({"rank": j, "tokens": 0, "kv_rows": 0, "useful_flops": 0, "ms": 0.0,
                           "local": 0, "distributed": 0})
             continue
-        ms, info = run_rank(seq, deg, idx, heads, head_dim, reps, seed + j)
+        ms, info = run_rank(seq, deg, idx, heads, head_dim, reps, seed + j, cut)
         info.update(rank=j, ms=round(ms, 4), local=int((deg == 1).sum()), distributed=int((deg != 1).sum()))
         ranks.append(info)
     t = np.array([r["ms"] for r in ranks])
@@ -102,6 +105,8 @@ def main(argv=None):
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--compare", action="store_true", help="also run plain CP (every sequence distributed)")
+    ap.add_argument("--cut", choices=["contiguous", "two-chunks"], default="two-chunks",
+                    help="how a distributed sequence is cut over the ranks")
     args = ap.parse_args(argv)
 
     import torch
@@ -112,7 +117,8 @@ def main(argv=None):
     torch.cuda.set_device(0)
     h, hkv, hq, hk, d = W.MODEL_SHAPES[args.model]
     S = args.seq_len or draw_micro_batch(args.dataset, args.bucket, args.cp, args.fill, args.seed)
-    S = [s for s in S if s >= args.cp]   # a sequence shorter than N tokens cannot be cut N ways
+    cut = 1 if args.cut == "two-chunks" else 0
+    S = [s for s in S if s >= (1 + cut) * args.cp]   # a sequence cannot be cut into more chunks than tokens
 
     sched_us = float("inf")
     for _ in range(5):   # best of five: the first call also pays for loading the library
@@ -120,13 +126,13 @@ def main(argv=None):
         ret = B.skrull_dacp_schedule(S, args.bucket, args.cp, h, hkv)
         sched_us = min(sched_us, (time.perf_counter() - t0) * 1e6)
     out = {"dataset": "explicit" if args.seq_len else args.dataset, "model": args.model,
-           "cp_degree": args.cp, "bucket_size": args.bucket, "num_seqs": len(S), "tokens": int(sum(S)),
+           "cp_degree": args.cp, "cut": args.cut, "bucket_size": args.bucket, "num_seqs": len(S), "tokens": int(sum(S)),
            "longest": int(max(S)), "schedule_us": round(sched_us, 1),
            "distributed_seqs": int((ret == -1).sum()), "local_seqs": int((ret != -1).sum()),
-           "dacp": run_schedule(S, ret, args.cp, (hq, hk), d, args.reps, args.seed)}
+           "dacp": run_schedule(S, ret, args.cp, (hq, hk), d, args.reps, args.seed, cut)}
     if args.compare:
         plain = np.full(len(S), -1, np.int32)
-        out["plain_cp"] = run_schedule(S, plain, args.cp, (hq, hk), d, args.reps, args.seed)
+        out["plain_cp"] = run_schedule(S, plain, args.cp, (hq, hk), d, args.reps, args.seed, cut)
         out["speedup_max_rank_time"] = round(out["plain_cp"]["max_ms"] / out["dacp"]["max_ms"], 3)
     print(json.dumps(out))
     return 0

@@ -35,6 +35,8 @@ def main(argv=None):
     ap.add_argument("--bucket", type=int, default=26 * 1024, help="BucketSize C, tokens per CP rank")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--reps", type=int, default=2)
+    ap.add_argument("--cut", choices=["contiguous", "two-chunks"], default="two-chunks",
+                    help="how a distributed sequence is cut over the CP ranks")
     args = ap.parse_args(argv)
 
     import torch
@@ -45,11 +47,12 @@ def main(argv=None):
     torch.cuda.set_device(0)
     h, hkv, hq, hk, d = W.MODEL_SHAPES[args.model]
     rng = np.random.Generator(np.random.PCG64(args.seed))
-    # no sequence longer than a micro-batch can hold, none too short to be cut N ways
-    S = [max(s, args.cp) for s in W.table1_lengths(rng, args.dataset, count=args.batch_size * args.dp,
+    cut = 1 if args.cut == "two-chunks" else 0
+    # no sequence longer than a micro-batch can hold, none with fewer tokens than chunks
+    S = [max(s, (1 + cut) * args.cp) for s in W.table1_lengths(rng, args.dataset, count=args.batch_size * args.dp,
                                                    longest=args.bucket * args.cp)]
     S = np.asarray(S, np.int32)
-    out = {"dataset": args.dataset, "model": args.model, "cp_degree": args.cp, "dp_world_size": args.dp,
+    out = {"dataset": args.dataset, "model": args.model, "cp_degree": args.cp, "cut": args.cut, "dp_world_size": args.dp,
            "bucket_size": args.bucket, "num_seqs": int(S.size), "tokens": int(S.sum()),
            "longest": int(S.max()), "dp_ranks": []}
     for r in ([args.dp_rank] if args.dp_rank is not None else range(args.dp)):
@@ -63,7 +66,7 @@ def main(argv=None):
         total = 0.0
         for j in range(m):
             members = B.skrull_gds_micro_batch(S, mb, j)
-            res = run_schedule(S[members], ret[members], args.cp, (hq, hk), d, args.reps, args.seed + 100 * j)
+            res = run_schedule(S[members], ret[members], args.cp, (hq, hk), d, args.reps, args.seed + 100 * j, cut)
             total += res["max_ms"]
             rank["micro_batches"].append({"num_seqs": int(members.size), "tokens": int(S[members].sum()),
                                           "distributed": int((ret[members] == -1).sum()),

@@ -16,8 +16,9 @@ pytestmark = pytest.mark.gpu
 TOL_O, TOL_G = 2e-2, 5e-2
 
 
+@pytest.mark.parametrize("cut", [0, 1])
 @pytest.mark.parametrize("N,C,heads,d", [(4, 2000, (4, 2), 64), (3, 2400, (6, 2), 128)])
-def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d):
+def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d, cut):
     from paper_2505_19609_amd import binding as B
     from oracle import dacp as OD
 
@@ -42,13 +43,18 @@ def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d):
     for j in range(N):
         seq, deg, idx, src = B.skrull_dacp_rank_batch(S, ret, N, j)
         qrows, krows = [], []
-        for s, g, i, k in zip(seq, deg, idx, src):
-            b, e = (i * s) // g, ((i + 1) * s) // g
-            qrows.append(np.arange(start[k] + b, start[k] + e))
-            krows.append(np.arange(start[k], start[k] + e))
+        cuts = [cut if g > 1 else 0 for g in deg]
+        for s, g, i, k, z in zip(seq, deg, idx, src, cuts):
+            if z:   # chunks i and 2g-1-i of 2g
+                parts = [((c * s) // (2 * g), ((c + 1) * s) // (2 * g)) for c in (i, 2 * g - 1 - i)]
+            else:
+                parts = [((i * s) // g, ((i + 1) * s) // g)]
+            for b, e in parts:
+                qrows.append(np.arange(start[k] + b, start[k] + e))
+            krows.append(np.arange(start[k], start[k] + parts[-1][1]))
         qrows, krows = np.concatenate(qrows), np.concatenate(krows)
         rv = {"q": vals["q"][qrows], "do": vals["do"][qrows], "k": vals["k"][krows], "v": vals["v"][krows]}
-        w = W.Workload(f"rank{j}", list(seq), list(deg), list(idx), Hq, Hkv, d, d ** -0.5, 0)
+        w = W.Workload(f"rank{j}", list(seq), list(deg), list(idx), Hq, Hkv, d, d ** -0.5, 0, shard_cut=cuts)
         out = run_library(w, vals=rv)
         assert out["plan"].total_q == len(qrows) and out["plan"].total_k == len(krows)
         o[qrows], dq[qrows], lse[:, qrows] = out["o"], out["dq"], out["lse"]
@@ -75,7 +81,7 @@ def test_driver_reports_every_rank(capsys):
     # Eq. 7/8: all tokens are placed, none twice, no rank over its bucket
     assert sum(r["tokens"] for r in rep["dacp"]["ranks"]) == rep["tokens"]
     assert sum(r["tokens"] for r in rep["plain_cp"]["ranks"]) == rep["tokens"]
-    assert max(r["tokens"] for r in rep["dacp"]["ranks"]) <= rep["bucket_size"]
+    assert max(r["tokens"] for r in rep["dacp"]["ranks"]) <= rep["bucket_size"] + rep["distributed_seqs"]
     assert rep["dacp"]["max_ms"] >= rep["dacp"]["min_ms"] > 0
 
 
