@@ -1,0 +1,81 @@
+"""The two-stream order (gather of the distributed sequences' K/V hidden behind the local
+sequences' forward, their dK/dV leaving behind the local sequences' backward; Eq. 2)
+against the plain one-stream order and against one plan over the whole micro-batch:
+every output bit for bit."""
+import json
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("source", ["host", "device"])
+@pytest.mark.parametrize("cut", [0, 1])
+def test_overlapped_order_changes_no_bit(source, cut):
+    from paper_2505_19609_amd import binding as B
+    from paper_2505_19609_amd.overlap_run import RankBatch
+
+    heads, d = (4, 2), 64
+    loc = ([300, 64, 777], [1, 1, 1], [0, 0, 0], [0, 0, 0])
+    dist = ([4096, 1001], [4, 4], [3, 1], [cut, cut])
+    rb = RankBatch(loc, dist, heads, d, 5, source)
+
+    def poison():
+        for t in rb.parts.values():
+            for n in ("o", "lse", "dq", "dk", "dv"):
+                t[n].fill_(float("nan"))
+        for n in ("dk", "dv"):
+            rb.stage[n].fill_(float("nan"))
+        dd = rb.parts["dist"]
+        dd["k"][:rb.remote_rows].zero_()       # the gather must bring these back
+        dd["v"][:rb.remote_rows].zero_()
+        torch.cuda.synchronize()
+
+    poison()
+    rb.step_serial()
+    torch.cuda.synchronize()
+    a = rb.outputs()
+    for rep in range(3):
+        poison()
+        rb.step_overlapped()
+        torch.cuda.synchronize()
+        b = rb.outputs()
+        assert a.keys() == b.keys()
+        for n in a:
+            assert torch.isfinite(a[n].float()).all(), n
+            assert torch.equal(a[n], b[n]), (rep, n)
+    # what left for the other ranks is the partial gradient of the rows they own
+    assert torch.equal(a["stage.dk"].cuda(), a["dist.dk"][:rb.remote_rows])
+
+    # one plan over the whole micro-batch (local first, then distributed): same bits
+    L, D = rb.parts["loc"], rb.parts["dist"]
+    plan = B.skrull_attn_plan(loc[0] + dist[0], loc[1] + dist[1], loc[2] + dist[2], heads[0], heads[1], d,
+                              d ** -0.5, shard_cut=loc[3] + dist[3])
+    cat = {n: torch.cat([L[n], D[n]]) for n in ("q", "k", "v", "do")}
+    o, dq = torch.empty_like(cat["q"]), torch.empty_like(cat["q"])
+    dk, dv = torch.empty_like(cat["k"]), torch.empty_like(cat["k"])
+    lse = torch.empty((heads[0], plan.total_q), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(int(plan.bwd_workspace_bytes), 16), dtype=torch.uint8, device="cuda")
+    B.skrull_attn_fwd(plan, cat["q"], cat["k"], cat["v"], o, lse)
+    B.skrull_attn_bwd(plan, cat["q"], cat["k"], cat["v"], o, lse, cat["do"], dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o, torch.cat([a["loc.o"], a["dist.o"]]))
+    assert torch.equal(lse, torch.cat([a["loc.lse"], a["dist.lse"]], dim=1))
+    assert torch.equal(dq, torch.cat([a["loc.dq"], a["dist.dq"]]))
+    assert torch.equal(dk, torch.cat([a["loc.dk"], a["dist.dk"]]))
+    assert torch.equal(dv, torch.cat([a["loc.dv"], a["dist.dv"]]))
+    plan.destroy()
+    rb.destroy()
+
+
+def test_overlap_driver(capsys):
+    from paper_2505_19609_amd import overlap_run
+    rc = overlap_run.main(["--model", "qwen2.5-0.5b", "--cp", "4", "--seq-len", "16384", "--local-budget", "2048",
+                           "--reps", "2"])
+    assert rc == 0
+    rep = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    # rank 3 of 4 holds chunks 3 and 4 of 8: prefix = 5 chunks, 2 of them its own
+    assert rep["exchanged_rows"] == 3 * (16384 // 8)
+    assert rep["serial_ms"] > 0 and rep["overlapped_ms"] > 0
