@@ -62,6 +62,7 @@ typedef struct {
     int32_t        block_m;       /* query rows per work item: 64, 128 or 256; 0 = 256          */
     int32_t        block_n;       /* key rows per dK/dV work item: 64, 128 or 256; 0 = 128      */
     const int32_t *shard_cut;     /* [K] HOST or NULL (= all SKRULL_CUT_CONTIGUOUS)             */
+    int32_t        head_split;    /* dK/dV workgroups per KV group, 1..Hq/Hkv; 0 = library's choice */
 } skrull_attn_problem_t;
 
 /*
@@ -93,7 +94,7 @@ typedef struct {
     int64_t useful_flops_bwd;     /* 10 * pairs * head_dim * Hq                                */
     int64_t bwd_workspace_bytes;  /* device scratch skrull_attn_bwd needs (>= 0)               */
     int32_t num_segments;         /* query segments: K + number of two-chunk sequences         */
-    int32_t reserved;
+    int32_t head_split;           /* the dK/dV head split in effect (>= 1)                     */
 } skrull_attn_plan_info_t;
 
 /* Arrays a plan holds on the device, for skrull_attn_plan_export.  They are per
@@ -133,7 +134,7 @@ enum {
  * number of fwd/bwd calls on any stream of the same device.
  * SKRULL_EINVAL: null pointer, K < 1, S_k < 1, degree < 1, index outside
  * [0, degree), more chunks than tokens (degree > S_k, or 2*degree > S_k for a
- * two-chunk cut), a cut other than the two above, Hq % Hkv != 0, head_dim not 64/128, a block size
+ * two-chunk cut), a cut other than the two above, head_split outside [0, Hq/Hkv], Hq % Hkv != 0, head_dim not 64/128, a block size
  * other than 0/64/128/256, scale not finite/positive, a total of 2^31 rows or
  * more, or more than 2^20 work items in either list.
  */
@@ -173,8 +174,10 @@ int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k
  * dK/dV of a shard are this rank's partial sums over its own query rows for
  * the whole prefix (a multi-GPU caller would reduce them across ranks; the
  * paper's Eq. 3/Volume(S) is that exchange).  All outputs bf16, rounded once
- * from fp32 accumulators; the group sum is done in registers (no atomics, so
- * results are bit-reproducible).
+ * from fp32 accumulators; the group sum is done in registers, or, when the plan's
+ * head_split is above 1, over fp32 partial sums in the workspace in a fixed order
+ * (no atomics either way, so results are bit-reproducible; two plans with
+ * different head_split may differ in the last bit of dK/dV).
  * `workspace` is DEVICE scratch of at least info.bwd_workspace_bytes, 16-byte
  * aligned; contents on entry are ignored and on exit unspecified.
  * Only enqueues on `hip_stream`; never synchronises.

@@ -39,7 +39,7 @@ bool g_ev_made = false, g_fwd_seen = false, g_bwd_seen = false;
 
 constexpr int32_t kMaxItems = 1 << 20;  // rank-counting sort is quadratic in the item count
 
-int check_device(int *dev_out)
+int check_device(int *dev_out, int *compute_units)
 {
     int n = 0;
     if (hipGetDeviceCount(&n) != hipSuccess || n < 1) {
@@ -52,6 +52,7 @@ int check_device(int *dev_out)
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return SKRULL_EUNSUPPORTED;
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return SKRULL_EUNSUPPORTED;
     *dev_out = dev;
+    *compute_units = prop.multiProcessorCount;
     return SKRULL_OK;
 }
 
@@ -72,6 +73,8 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     const int32_t BN = p->block_n == 0 ? 128 : p->block_n;
     if ((BM != 64 && BM != 128 && BM != 256) || (BN != 64 && BN != 128 && BN != 256))
         return SKRULL_EINVAL;
+    const int32_t group = p->num_q_heads / p->num_kv_heads;
+    if (p->head_split < 0 || p->head_split > group) return SKRULL_EINVAL;
     // Entry checks that need no arithmetic are done here so that they work
     // without a device; the kernel repeats them next to the range computation.
     int64_t n_seg = 0;  // query segments: a two-chunk cut contributes two
@@ -83,8 +86,8 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         n_seg += 1 + z;
     }
     if (n_seg > INT32_MAX / 2) return SKRULL_EINVAL;
-    int dev = 0;
-    int rc = check_device(&dev);
+    int dev = 0, compute_units = 0;
+    int rc = check_device(&dev, &compute_units);
     if (rc != SKRULL_OK) return rc;
 
     hipStream_t st = (hipStream_t)hip_stream;
@@ -146,8 +149,22 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         plan->dkv_items = plan->fwd_items + 4 * (int64_t)plan->n_fwd;
         HIP_TRY(hipMalloc((void **)&scratch, item_bytes));
         HIP_TRY(launch_plan_items(plan, fwd_off, dkv_off, scratch,
-                                  scratch + 4 * (int64_t)plan->n_fwd, st));
+                                  scratch + 4 * (int64_t)plan->n_fwd, totals_d, st));
+        HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));
+    }
+    // dK/dV head split.  A workgroup of that kernel walks all query tiles of one key
+    // block for every query head of the KV group, one after another; its longest chain
+    // is cost_max * group.  Spread evenly, the whole list is cost_sum * group * Hkv over
+    // the compute units.  When the longest chain exceeds that share (few KV heads, one
+    // long sequence in a small micro-batch) the heads of a group are shared out over
+    // several workgroups until it no longer does, with a factor two of slack.
+    plan->head_split = p->head_split;
+    if (plan->head_split == 0) {
+        const double share = (double)totals.dkv_cost_sum * plan->Hkv / (double)compute_units;
+        const double want = share > 0.0 ? 2.0 * (double)totals.dkv_cost_max / share : 1.0;
+        int32_t hs = want <= 1.0 ? 1 : (want >= (double)group ? group : (int32_t)ceil(want));
+        plan->head_split = hs < 1 ? 1 : (hs > group ? group : hs);
     }
     rc = SKRULL_OK;
 done:
@@ -183,8 +200,10 @@ int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_
     info->useful_flops_fwd = 4 * plan->pairs * plan->d * plan->Hq;
     info->useful_flops_bwd = 10 * plan->pairs * plan->d * plan->Hq;
     info->bwd_workspace_bytes = (((int64_t)plan->Hq * plan->total_q * 8) + 255) & ~(int64_t)255;
+    if (plan->head_split > 1)  // fp32 partial dK and dV of every share of the heads
+        info->bwd_workspace_bytes += 2 * (int64_t)plan->head_split * plan->total_k * plan->Hkv * plan->d * 4;
     info->num_segments = plan->NS;
-    info->reserved = 0;
+    info->head_split = plan->head_split;
     return SKRULL_OK;
 }
 

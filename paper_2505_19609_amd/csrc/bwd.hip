@@ -75,6 +75,11 @@ struct BwdParams {
     const int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len, *shares_kv;
     int32_t Hq, Hkv, total_q, BM, BN;
     float scale, scale_log2;
+    // dK/dV head split: the query heads of a KV group are shared out over `head_split`
+    // workgroups, which leave unrounded partial sums in dk_part / dv_part
+    // ([head_split][total_k][Hkv][D] fp32) for dkv_reduce_kernel; 1 = no split
+    int32_t head_split, total_k;
+    float *dk_part, *dv_part;
 };
 
 // ---------------------------------------------------------------------------
@@ -292,8 +297,12 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
     // key rows is two workgroups
     const int passes = (prm.BN + SUB - 1) / SUB;
     const int sub = blockIdx.x % passes;
-    const int item_id = (blockIdx.x / passes) / prm.Hkv, c = (blockIdx.x / passes) % prm.Hkv;
-    const int g = prm.Hq / prm.Hkv;
+    const int hs = prm.head_split;
+    const int hp = (blockIdx.x / passes) % hs;  // which share of the group's query heads
+    const int c = (blockIdx.x / passes / hs) % prm.Hkv, item_id = blockIdx.x / passes / hs / prm.Hkv;
+    const int g_all = prm.Hq / prm.Hkv;
+    const int head_lo = (hp * g_all) / hs;
+    const int g = ((hp + 1) * g_all) / hs - head_lo;  // >= 1 since head_split <= g_all
     FragAddr<D> fa;
     fa.init(lane);
     RingLoader<D, NWP> ld;
@@ -350,7 +359,7 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
 
     // fetch of tile (head th of the group, query tile tq_idx) into ring slot `slot`
     auto fetch = [&](int th, int tq_idx, int slot) __attribute__((always_inline)) {
-        const int head = c * g + th;
+        const int head = c * g_all + head_lo + th;
         const int i0 = tile_i0(tq_idx);
         const int rows = tile_ql(tq_idx);
         const int first_row = tq_idx < n_qt_e ? qbase_e : qbase;
@@ -636,9 +645,31 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
     }
     if (wave_active && my_j < kvl) {
         const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
-        if (role == 0) store_rows_bf16<TT>(prm.dv + off, acc, 1.0f, h);
-        else store_rows_bf16<TT>(prm.dk + off, acc, prm.scale, h);
+        if (hs == 1) {
+            if (role == 0) store_rows_bf16<TT>(prm.dv + off, acc, 1.0f, h);
+            else store_rows_bf16<TT>(prm.dk + off, acc, prm.scale, h);
+        } else {
+            const size_t part = (size_t)hp * prm.total_k * prm.Hkv * D;
+            store_rows_f32<TT>((role == 0 ? prm.dv_part : prm.dk_part) + part + off, acc, h);
+        }
     }
+}
+
+// Sum of the head-split partial gradients, rounded once: out = bf16(mul * sum_p part[p]).
+__global__ __launch_bounds__(256) void dkv_reduce_kernel(const float *__restrict__ part, int32_t parts,
+                                                         int64_t n4, float mul, uint16_t *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    float4 a = ((const float4 *)part)[i];
+    for (int32_t p = 1; p < parts; ++p) {
+        const float4 b = ((const float4 *)part)[(int64_t)p * n4 + i];
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    uint2 w;
+    w.x = pack_bf16(a.x * mul, a.y * mul);
+    w.y = pack_bf16(a.z * mul, a.w * mul);
+    ((uint2 *)out)[i] = w;
 }
 
 template <int D>
@@ -653,10 +684,19 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const voi
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    const int gq = p->n_fwd * p->Hq, gk = p->n_dkv * p->Hkv * ((p->BN + SUB - 1) / SUB);
+    const int gq = p->n_fwd * p->Hq;
+    const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + SUB - 1) / SUB);
     dkv_kernel<D><<<gk, 64 * NWP, 0, st>>>(prm);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (p->head_split > 1) {
+        const int64_t n4 = (int64_t)p->total_k * p->Hkv * D / 4;
+        const unsigned blocks = (unsigned)((n4 + 255) / 256);
+        dkv_reduce_kernel<<<blocks, 256, 0, st>>>(prm.dk_part, p->head_split, n4, prm.scale, prm.dk);
+        dkv_reduce_kernel<<<blocks, 256, 0, st>>>(prm.dv_part, p->head_split, n4, 1.0f, prm.dv);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (ev) (void)hipEventRecord(ev[2], st);
     dq_kernel<D><<<gq, 64 * NW, 0, st>>>(prm);
     if (ev) (void)hipEventRecord(ev[3], st);
@@ -679,6 +719,13 @@ hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     prm.kv_len = p->kv_len; prm.shares_kv = p->shares_kv;
     prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM; prm.BN = p->BN;
     prm.scale = p->scale; prm.scale_log2 = p->scale * kLog2e;
+    prm.head_split = p->head_split; prm.total_k = p->total_k;
+    {
+        // workspace: -D | LSE*log2e | (256-byte aligned) dK partials | dV partials
+        const size_t rows = (((size_t)p->Hq * p->total_q * 8) + 255) & ~(size_t)255;
+        prm.dk_part = (float *)((char *)delta + rows);
+        prm.dv_part = prm.dk_part + (size_t)p->head_split * p->total_k * p->Hkv * p->d;
+    }
     if (p->d == 128) return launch_d<128>(p, prm, o, delta, st, ev);
     if (p->d == 64) return launch_d<64>(p, prm, o, delta, st, ev);
     return hipErrorInvalidValue;

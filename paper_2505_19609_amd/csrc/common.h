@@ -13,6 +13,7 @@ struct skrull_attn_plan {
     float scale;
     int32_t total_q, total_k, n_fwd, n_dkv;
     int64_t pairs;
+    int32_t head_split;  // workgroups that share the query heads of one KV group in dK/dV
     int device;
     // one allocation; the pointers below index into it
     int32_t *pool;
@@ -25,6 +26,9 @@ struct PlanTotals {
     int64_t total_q, total_k, n_fwd, n_dkv, pairs;
     int32_t bad_entry;   // index+1 of the first invalid sequence, 0 if none
     int32_t n_seg;       // number of query segments
+    // cost (query blocks) of the dK/dV items, accumulated by the emit kernel
+    unsigned long long dkv_cost_sum;
+    int32_t dkv_cost_max, pad;
 };
 
 // plan.hip
@@ -36,7 +40,7 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
                               PlanTotals *totals, hipStream_t st);
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
                              const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
-                             hipStream_t st);
+                             PlanTotals *totals, hipStream_t st);
 
 // fwd.hip / bwd.hip
 hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,

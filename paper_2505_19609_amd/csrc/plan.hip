@@ -130,6 +130,9 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
         totals->pairs = pairs;
         totals->bad_entry = (first_bad == 0x7fffffff) ? 0 : first_bad + 1;
         totals->n_seg = (int32_t)base_s;
+        totals->dkv_cost_sum = 0;
+        totals->dkv_cost_max = 0;
+        totals->pad = 0;
     }
 }
 
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(256) void plan_emit_kernel(
     const int32_t *__restrict__ cu_q, const int32_t *__restrict__ shares_kv,
     const int32_t *__restrict__ fwd_off,
     const int32_t *__restrict__ dkv_off, int32_t n_fwd, int32_t n_dkv,
-    int4 *__restrict__ fwd_items, int4 *__restrict__ dkv_items)
+    int4 *__restrict__ fwd_items, int4 *__restrict__ dkv_items, PlanTotals *__restrict__ totals)
 {
     const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n_fwd) {
@@ -177,6 +180,8 @@ __global__ __launch_bounds__(256) void plan_emit_kernel(
             cost += (int32_t)ceil_div64(q_len[k - 1], BM) - (int32_t)(j0 / BM);
         }
         dkv_items[t] = make_int4(k, b, m0, cost);
+        atomicAdd(&totals->dkv_cost_sum, (unsigned long long)cost);
+        atomicMax(&totals->dkv_cost_max, cost);
     }
 }
 
@@ -222,12 +227,12 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
 
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
                              const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
-                             hipStream_t st)
+                             PlanTotals *totals, hipStream_t st)
 {
     const int32_t n = p->n_fwd > p->n_dkv ? p->n_fwd : p->n_dkv;
     plan_emit_kernel<<<(n + 255) / 256, 256, 0, st>>>(
         p->NS, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off, p->n_fwd,
-        p->n_dkv, (int4 *)scratch_fwd, (int4 *)scratch_dkv);
+        p->n_dkv, (int4 *)scratch_fwd, (int4 *)scratch_dkv, totals);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     plan_sort_kernel<<<(p->n_fwd + 255) / 256, 256, 0, st>>>((const int4 *)scratch_fwd, p->n_fwd,

@@ -236,6 +236,18 @@ __device__ __forceinline__ void store_rows_bf16(uint16_t *dst, const f32x16 (&ac
         }
 }
 
+// The same tile set as unrounded fp32 rows of a [rows, H, D] float tensor.
+template <int TT>
+__device__ __forceinline__ void store_rows_f32(float *dst, const f32x16 (&acc)[TT], int h)
+{
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb)
+            *(float4 *)(dst + 32 * tt + 8 * vb + 4 * h) =
+                make_float4(acc[tt][4 * vb + 0], acc[tt][4 * vb + 1], acc[tt][4 * vb + 2], acc[tt][4 * vb + 3]);
+}
+
 template <int N>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[N])
 {

@@ -31,7 +31,7 @@ class RankBatch:
     """Device tensors and plans of one rank's share: `loc` = whole sequences,
     `dist` = its slices of distributed ones."""
 
-    def __init__(self, loc, dist, heads, head_dim, seed, source):
+    def __init__(self, loc, dist, heads, head_dim, seed, source, head_split=0):
         import torch
         from . import binding as B
         self.B, self.torch = B, torch
@@ -42,7 +42,8 @@ class RankBatch:
             if len(S) == 0:
                 self.parts[name] = None
                 continue
-            plan = B.skrull_attn_plan(S, deg, idx, hq, hkv, head_dim, head_dim ** -0.5, shard_cut=cut)
+            plan = B.skrull_attn_plan(S, deg, idx, hq, hkv, head_dim, head_dim ** -0.5, shard_cut=cut,
+                                     head_split=head_split)
             tq, tk = plan.total_q, plan.total_k
 
             def rnd(rows, h):

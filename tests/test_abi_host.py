@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol(B):
 
 
 def test_struct_layouts_match_header(B):
-    # 4+pad, 3 pointers, 3 ints, float, 2 ints, 1 pointer
-    assert ctypes.sizeof(B.Problem) == 64
+    # 4+pad, 3 pointers, 3 ints, float, 2 ints, 1 pointer, 1 int + pad
+    assert ctypes.sizeof(B.Problem) == 72
     assert ctypes.sizeof(B.PlanInfo) == 10 * 4 + 4 * 8 + 2 * 4
 
 

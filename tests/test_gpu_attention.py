@@ -30,8 +30,8 @@ def _report(name, got, ref, tol):
     return float(err[i])
 
 
-def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G):
-    out = run_library(w, block_m, block_n)
+def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G, head_split=0):
+    out = run_library(w, block_m, block_n, head_split=head_split)
     f = widen(out["vals"])
     desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index, w.shard_cut)
     O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
@@ -341,3 +341,30 @@ def test_two_chunk_cut_equals_its_two_slices_at_full_length():
     # the pairs this rank attends are 1/N of the sequence's, up to rounding
     assert abs(z["plan"].attended_pairs - S * (S + 1) // 2 // N) <= 2 * S
     z["plan"].destroy()
+
+
+# ---------------------------------------------------------------------------
+# dK/dV head split: the query heads of a KV group shared out over several workgroups
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("heads,split", [((14, 2), 1), ((14, 2), 2), ((14, 2), 3), ((14, 2), 7),
+                                         ((8, 2), 4), ((6, 6), 1), ((4, 1), 3)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_head_split(oracle, heads, split, d):
+    w = W.Workload("split", [700, 129, 2100, 64, 1500], [1, 1, 3, 1, 2], [0, 0, 1, 0, 1], heads[0], heads[1],
+                   d, d ** -0.5, 88, shard_cut=[0, 0, 1, 0, 0])
+    _exhaustive(oracle, w, head_split=split)
+
+
+def test_head_split_is_chosen_from_the_work_list():
+    from paper_2505_19609_amd import binding as B
+    w2, w3 = W.config(2), W.config(3)
+    p2 = B.skrull_attn_plan(w2.seq_len, w2.shard_degree, w2.shard_index, 14, 2, 64, 0.125)
+    p3 = B.skrull_attn_plan(w3.seq_len, w3.shard_degree, w3.shard_index, 32, 8, 128, 0.1)
+    base2 = (14 * p2.total_q * 8 + 255) // 256 * 256
+    assert 1 < p2.head_split <= 7      # two KV heads and one long sequence: too few workgroups
+    assert p2.bwd_workspace_bytes == base2 + 2 * p2.head_split * p2.total_k * 2 * 64 * 4
+    assert p3.head_split == 1          # plenty of parallelism: the register-only path
+    for bad in (-1, 8):
+        with pytest.raises(B.SkrullError):
+            B.skrull_attn_plan(w2.seq_len, w2.shard_degree, w2.shard_index, 14, 2, 64, 0.125, head_split=bad)
+    p2.destroy(); p3.destroy()

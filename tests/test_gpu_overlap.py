@@ -20,7 +20,7 @@ def test_overlapped_order_changes_no_bit(source, cut):
     heads, d = (4, 2), 64
     loc = ([300, 64, 777], [1, 1, 1], [0, 0, 0], [0, 0, 0])
     dist = ([4096, 1001], [4, 4], [3, 1], [cut, cut])
-    rb = RankBatch(loc, dist, heads, d, 5, source)
+    rb = RankBatch(loc, dist, heads, d, 5, source, head_split=1)   # as the one-plan run below
 
     def poison():
         for t in rb.parts.values():
@@ -52,7 +52,7 @@ def test_overlapped_order_changes_no_bit(source, cut):
     # one plan over the whole micro-batch (local first, then distributed): same bits
     L, D = rb.parts["loc"], rb.parts["dist"]
     plan = B.skrull_attn_plan(loc[0] + dist[0], loc[1] + dist[1], loc[2] + dist[2], heads[0], heads[1], d,
-                              d ** -0.5, shard_cut=loc[3] + dist[3])
+                              d ** -0.5, shard_cut=loc[3] + dist[3], head_split=1)
     cat = {n: torch.cat([L[n], D[n]]) for n in ("q", "k", "v", "do")}
     o, dq = torch.empty_like(cat["q"]), torch.empty_like(cat["q"])
     dk, dv = torch.empty_like(cat["k"]), torch.empty_like(cat["k"])
