@@ -75,29 +75,41 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         return SKRULL_EINVAL;
     const int32_t group = p->num_q_heads / p->num_kv_heads;
     if (p->head_split < 0 || p->head_split > group) return SKRULL_EINVAL;
-    // Entry checks that need no arithmetic are done here so that they work
-    // without a device; the kernel repeats them next to the range computation.
+    // Entry checks are done here so that they work without a device; the kernel repeats
+    // them next to the range computation.  The same pass bounds the number of work
+    // items from above (chunk lengths differ by at most one row; a prefix is no longer
+    // than its sequence), which sizes the allocations and the grids, so that the whole
+    // plan is built with one copy in, one copy out and one synchronisation.
     int64_t n_seg = 0;  // query segments: a two-chunk cut contributes two
+    int64_t cap_fwd = 0, cap_dkv = 0;
     for (int32_t k = 0; k < K; ++k) {
         const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
         const int32_t z = p->shard_cut ? p->shard_cut[k] : SKRULL_CUT_CONTIGUOUS;
         if (z != SKRULL_CUT_CONTIGUOUS && z != SKRULL_CUT_TWO_CHUNKS) return SKRULL_EINVAL;
         if (s < 1 || n < 1 || r < 0 || r >= n || (int64_t)n * (1 + z) > s) return SKRULL_EINVAL;
         n_seg += 1 + z;
+        const int64_t chunks = (int64_t)n * (1 + z), longest = (s + chunks - 1) / chunks;
+        cap_fwd += (1 + z) * ((longest + BM - 1) / BM);
+        cap_dkv += ((int64_t)s + BN - 1) / BN;
     }
     if (n_seg > INT32_MAX / 2) return SKRULL_EINVAL;
+    if (cap_fwd > 8 * (int64_t)kMaxItems || cap_dkv > 8 * (int64_t)kMaxItems) return SKRULL_EINVAL;
     int dev = 0, compute_units = 0;
     int rc = check_device(&dev, &compute_units);
     if (rc != SKRULL_OK) return rc;
 
     hipStream_t st = (hipStream_t)hip_stream;
     skrull_attn_plan_t *plan = nullptr;
-    int32_t *tmp = nullptr, *scratch = nullptr, *fwd_off = nullptr, *dkv_off = nullptr;
-    PlanTotals *totals_d = nullptr;
+    int32_t *tmp = nullptr, *host_in = nullptr;
     PlanTotals totals;
-    // tmp: S, N, R, cut [K each], fwd_off, dkv_off [n_seg+1 each]
+    // tmp (released before return): S, N, R, cut [K each] | fwd_off, dkv_off [n_seg+1 each] |
+    // totals | unsorted items
     const int64_t kin = align4(K), kpad = align4(n_seg + 1);
+    const int64_t totals_ints = align4((int64_t)((sizeof(PlanTotals) + 3) / 4));
+    const int64_t tmp_ints = 4 * kin + 2 * kpad + totals_ints + 4 * (cap_fwd + cap_dkv);
     const int64_t desc_ints = 6 * kpad;
+    int32_t *fwd_off = nullptr, *dkv_off = nullptr, *scratch = nullptr;
+    PlanTotals *totals_d = nullptr;
 
     plan = new (std::nothrow) skrull_attn_plan_t();
     if (!plan) return SKRULL_ENOMEM;
@@ -105,35 +117,41 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     plan->K = K; plan->NS = (int32_t)n_seg; plan->Hq = p->num_q_heads; plan->Hkv = p->num_kv_heads; plan->d = p->head_dim;
     plan->BM = BM; plan->BN = BN; plan->scale = p->softmax_scale; plan->device = dev;
 
-    HIP_TRY(hipMalloc((void **)&tmp, (size_t)(4 * kin + 2 * kpad) * sizeof(int32_t)));
-    HIP_TRY(hipMalloc((void **)&totals_d, sizeof(PlanTotals)));
-    HIP_TRY(hipMalloc((void **)&plan->pool, (size_t)desc_ints * sizeof(int32_t)));
+    host_in = (int32_t *)calloc((size_t)(4 * kin), sizeof(int32_t));
+    if (!host_in) { rc = SKRULL_ENOMEM; goto done; }
+    memcpy(host_in, p->seq_len, (size_t)K * 4);
+    memcpy(host_in + kin, p->shard_degree, (size_t)K * 4);
+    memcpy(host_in + 2 * kin, p->shard_index, (size_t)K * 4);
+    if (p->shard_cut) memcpy(host_in + 3 * kin, p->shard_cut, (size_t)K * 4);
+
+    HIP_TRY(hipMalloc((void **)&tmp, (size_t)tmp_ints * sizeof(int32_t)));
+    HIP_TRY(hipMalloc((void **)&plan->pool, (size_t)(desc_ints + 4 * (cap_fwd + cap_dkv)) * sizeof(int32_t)));
     plan->cu_q = plan->pool;
     plan->cu_k = plan->pool + kpad;
     plan->q_begin = plan->pool + 2 * kpad;
     plan->q_len = plan->pool + 3 * kpad;
     plan->kv_len = plan->pool + 4 * kpad;
     plan->shares_kv = plan->pool + 5 * kpad;
-    HIP_TRY(hipMemcpyAsync(tmp, p->seq_len, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(tmp + kin, p->shard_degree, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(tmp + 2 * kin, p->shard_index, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    if (p->shard_cut) {
-        HIP_TRY(hipMemcpyAsync(tmp + 3 * kin, p->shard_cut, (size_t)K * 4, hipMemcpyHostToDevice, st));
-    } else {
-        HIP_TRY(hipMemsetAsync(tmp + 3 * kin, 0, (size_t)K * 4, st));
-    }
+    plan->fwd_items = plan->pool + desc_ints;
+    plan->dkv_items = plan->fwd_items + 4 * cap_fwd;
     fwd_off = tmp + 4 * kin;
     dkv_off = fwd_off + kpad;
+    totals_d = (PlanTotals *)(dkv_off + kpad);
+    scratch = dkv_off + kpad + totals_ints;
+    // a pageable source is staged by the runtime before the call returns
+    HIP_TRY(hipMemcpyAsync(tmp, host_in, (size_t)(4 * kin) * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(launch_plan_ranges(tmp, tmp + kin, tmp + 2 * kin, tmp + 3 * kin, K, BM, BN,
                                INT32_MAX / (p->num_q_heads * p->head_dim),
                                INT32_MAX / (p->num_kv_heads * p->head_dim), plan->q_begin,
                                plan->q_len, plan->kv_len, plan->cu_q, plan->cu_k, plan->shares_kv,
-                               fwd_off, dkv_off, totals_d, st));
+                               fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, totals_d, st));
+    HIP_TRY(launch_plan_items(plan, fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, scratch,
+                              scratch + 4 * cap_fwd, totals_d, st));
     HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (totals.bad_entry != 0 || totals.n_seg != plan->NS || totals.total_q > INT32_MAX ||
-        totals.total_k > INT32_MAX ||
-        totals.n_fwd > kMaxItems || totals.n_dkv > kMaxItems) {
+        totals.total_k > INT32_MAX || totals.n_fwd > kMaxItems || totals.n_dkv > kMaxItems ||
+        totals.n_fwd > cap_fwd || totals.n_dkv > cap_dkv) {
         snprintf(g_err, sizeof g_err, "micro-batch too large or invalid entry %d", totals.bad_entry - 1);
         rc = SKRULL_EINVAL;
         goto done;
@@ -143,16 +161,6 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     plan->n_fwd = (int32_t)totals.n_fwd;
     plan->n_dkv = (int32_t)totals.n_dkv;
     plan->pairs = totals.pairs;
-    {
-        const size_t item_bytes = (size_t)(plan->n_fwd + plan->n_dkv) * 16;
-        HIP_TRY(hipMalloc((void **)&plan->fwd_items, item_bytes));
-        plan->dkv_items = plan->fwd_items + 4 * (int64_t)plan->n_fwd;
-        HIP_TRY(hipMalloc((void **)&scratch, item_bytes));
-        HIP_TRY(launch_plan_items(plan, fwd_off, dkv_off, scratch,
-                                  scratch + 4 * (int64_t)plan->n_fwd, totals_d, st));
-        HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipStreamSynchronize(st));
-    }
     // dK/dV head split.  A workgroup of that kernel walks all query tiles of one key
     // block for every query head of the KV group, one after another; its longest chain
     // is cost_max * group.  Spread evenly, the whole list is cost_sum * group * Hkv over
@@ -168,13 +176,11 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     }
     rc = SKRULL_OK;
 done:
+    free(host_in);
     if (tmp) (void)hipFree(tmp);
-    if (totals_d) (void)hipFree(totals_d);
-    if (scratch) (void)hipFree(scratch);
     if (rc != SKRULL_OK) {
         if (plan) {
             if (plan->pool) (void)hipFree(plan->pool);
-            if (plan->fwd_items) (void)hipFree(plan->fwd_items);
             delete plan;
         }
         return rc;
@@ -265,7 +271,6 @@ void skrull_attn_plan_destroy(skrull_attn_plan_t *plan)
 {
     if (!plan) return;
     if (plan->pool) (void)hipFree(plan->pool);
-    if (plan->fwd_items) (void)hipFree(plan->fwd_items);
     delete plan;
 }
 

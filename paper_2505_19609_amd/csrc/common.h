@@ -15,7 +15,7 @@ struct skrull_attn_plan {
     int64_t pairs;
     int32_t head_split;  // workgroups that share the query heads of one KV group in dK/dV
     int device;
-    // one allocation; the pointers below index into it
+    // one allocation (descriptor arrays, then the two item lists); the pointers below index into it
     int32_t *pool;
     int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len, *shares_kv;  // per segment: [NS+1] x2, [NS] x4
     int32_t *fwd_items, *dkv_items;                   // [n][4], sorted
@@ -28,7 +28,9 @@ struct PlanTotals {
     int32_t n_seg;       // number of query segments
     // cost (query blocks) of the dK/dV items, accumulated by the emit kernel
     unsigned long long dkv_cost_sum;
-    int32_t dkv_cost_max, pad;
+    int32_t dkv_cost_max;
+    int32_t cap_fwd, cap_dkv;  // room in the item arrays (the host's upper bounds)
+    int32_t pad;
 };
 
 // plan.hip
@@ -37,10 +39,11 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
                               int32_t max_q_rows, int32_t max_k_rows, int32_t *q_begin,
                               int32_t *q_len, int32_t *kv_len, int32_t *cu_q, int32_t *cu_k,
                               int32_t *shares_kv, int32_t *fwd_off, int32_t *dkv_off,
-                              PlanTotals *totals, hipStream_t st);
+                              int32_t cap_fwd, int32_t cap_dkv, PlanTotals *totals, hipStream_t st);
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
-                             const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
-                             PlanTotals *totals, hipStream_t st);
+                             const int32_t *dkv_off, int32_t cap_fwd, int32_t cap_dkv,
+                             int32_t *scratch_fwd, int32_t *scratch_dkv, PlanTotals *totals,
+                             hipStream_t st);
 
 // fwd.hip / bwd.hip
 hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,

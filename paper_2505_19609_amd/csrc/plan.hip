@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
     int32_t max_k_rows, int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
     int32_t *__restrict__ kv_len, int32_t *__restrict__ cu_q, int32_t *__restrict__ cu_k,
     int32_t *__restrict__ shares_kv, int32_t *__restrict__ fwd_off, int32_t *__restrict__ dkv_off,
-    PlanTotals *__restrict__ totals)
+    int32_t cap_fwd, int32_t cap_dkv, PlanTotals *__restrict__ totals)
 {
     __shared__ int64_t lds[kScanThreads];
     __shared__ int32_t first_bad;
@@ -132,6 +132,8 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
         totals->n_seg = (int32_t)base_s;
         totals->dkv_cost_sum = 0;
         totals->dkv_cost_max = 0;
+        totals->cap_fwd = cap_fwd;
+        totals->cap_dkv = cap_dkv;
         totals->pad = 0;
     }
 }
@@ -152,9 +154,13 @@ __global__ __launch_bounds__(256) void plan_emit_kernel(
     const int32_t *__restrict__ q_len, const int32_t *__restrict__ kv_len,
     const int32_t *__restrict__ cu_q, const int32_t *__restrict__ shares_kv,
     const int32_t *__restrict__ fwd_off,
-    const int32_t *__restrict__ dkv_off, int32_t n_fwd, int32_t n_dkv,
-    int4 *__restrict__ fwd_items, int4 *__restrict__ dkv_items, PlanTotals *__restrict__ totals)
+    const int32_t *__restrict__ dkv_off, int4 *__restrict__ fwd_items,
+    int4 *__restrict__ dkv_items, PlanTotals *__restrict__ totals)
 {
+    // the grid covers an upper bound of the item counts; the counts themselves are the
+    // ranges kernel's (clamped: a count past the limit is rejected by the host afterwards)
+    const int32_t n_fwd = (int32_t)min((long long)totals->n_fwd, (long long)totals->cap_fwd);
+    const int32_t n_dkv = (int32_t)min((long long)totals->n_dkv, (long long)totals->cap_dkv);
     const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n_fwd) {
         const int32_t k = owner_of(fwd_off, K, t);
@@ -189,10 +195,13 @@ __global__ __launch_bounds__(256) void plan_emit_kernel(
 //   #{b : cost_b > cost_a} + #{b < a : cost_b == cost_a}.
 // Costs are streamed through LDS in tiles; every thread of a block walks the
 // same tile, so the reads are broadcasts.
-__global__ __launch_bounds__(256) void plan_sort_kernel(const int4 *__restrict__ in, int32_t n,
-                                                        int4 *__restrict__ out)
+__global__ __launch_bounds__(256) void plan_sort_kernel(const int4 *__restrict__ in,
+                                                        const PlanTotals *__restrict__ totals,
+                                                        int which, int4 *__restrict__ out)
 {
     __shared__ int32_t tile[1024];
+    const int32_t n = which == 0 ? (int32_t)min((long long)totals->n_fwd, (long long)totals->cap_fwd)
+                                 : (int32_t)min((long long)totals->n_dkv, (long long)totals->cap_dkv);
     const int32_t a = blockIdx.x * blockDim.x + threadIdx.x;
     const int4 me = (a < n) ? in[a] : make_int4(0, 0, 0, 0);
     int32_t rank = 0;
@@ -217,29 +226,32 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
                               int32_t max_q_rows, int32_t max_k_rows, int32_t *q_begin,
                               int32_t *q_len, int32_t *kv_len, int32_t *cu_q, int32_t *cu_k,
                               int32_t *shares_kv, int32_t *fwd_off, int32_t *dkv_off,
-                              PlanTotals *totals, hipStream_t st)
+                              int32_t cap_fwd, int32_t cap_dkv, PlanTotals *totals, hipStream_t st)
 {
     plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, cut, K, BM, BN, max_q_rows, max_k_rows,
                                                    q_begin, q_len, kv_len, cu_q, cu_k, shares_kv,
-                                                   fwd_off, dkv_off, totals);
+                                                   fwd_off, dkv_off, cap_fwd, cap_dkv, totals);
     return hipGetLastError();
 }
 
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
-                             const int32_t *dkv_off, int32_t *scratch_fwd, int32_t *scratch_dkv,
-                             PlanTotals *totals, hipStream_t st)
+                             const int32_t *dkv_off, int32_t cap_fwd, int32_t cap_dkv,
+                             int32_t *scratch_fwd, int32_t *scratch_dkv, PlanTotals *totals,
+                             hipStream_t st)
 {
-    const int32_t n = p->n_fwd > p->n_dkv ? p->n_fwd : p->n_dkv;
+    // grids are sized by the host's upper bounds of the item counts; the kernels take the
+    // counts from `totals` on the device, so no round trip to the host is needed in between
+    const int32_t n = cap_fwd > cap_dkv ? cap_fwd : cap_dkv;
     plan_emit_kernel<<<(n + 255) / 256, 256, 0, st>>>(
-        p->NS, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off, p->n_fwd,
-        p->n_dkv, (int4 *)scratch_fwd, (int4 *)scratch_dkv, totals);
+        p->NS, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off,
+        (int4 *)scratch_fwd, (int4 *)scratch_dkv, totals);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    plan_sort_kernel<<<(p->n_fwd + 255) / 256, 256, 0, st>>>((const int4 *)scratch_fwd, p->n_fwd,
-                                                             (int4 *)p->fwd_items);
+    plan_sort_kernel<<<(cap_fwd + 255) / 256, 256, 0, st>>>((const int4 *)scratch_fwd, totals, 0,
+                                                            (int4 *)p->fwd_items);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    plan_sort_kernel<<<(p->n_dkv + 255) / 256, 256, 0, st>>>((const int4 *)scratch_dkv, p->n_dkv,
-                                                             (int4 *)p->dkv_items);
+    plan_sort_kernel<<<(cap_dkv + 255) / 256, 256, 0, st>>>((const int4 *)scratch_dkv, totals, 1,
+                                                            (int4 *)p->dkv_items);
     return hipGetLastError();
 }
