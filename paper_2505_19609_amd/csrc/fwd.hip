@@ -47,7 +47,7 @@ struct FwdParams {
 
 constexpr int NW = 8;          // wavefronts per workgroup
 constexpr int SUB = 32 * NW;   // query rows per workgroup (the largest block_m)
-constexpr int NSLOT = 3;       // ring slots per operand
+constexpr int NSLOT = 4;  // ring slots per operand: two tiles being read, two being fetched
 
 
 // max / sum of a value over the two halves of the wavefront (lanes l and l ^ 32)
@@ -140,8 +140,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     Loader ld;
     ld.init(lane, wave, (uint32_t)prm.Hkv * D * 2);
     const uint32_t ring_k = lds_addr(&lds_k[0][0]), ring_v = lds_addr(&lds_v[0][0]);
-    // asynchronous loads this wave issues per tile (its share of the 64-slot groups)
-    const bool big_share = wave < Loader::GROUPS - (Loader::PER - 1) * NW;
 
     const int4 it = prm.items[item_id];
     const int seq = it.x;
@@ -300,19 +298,19 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         }
     };
 
-    // fetch group of period t: K tile t+2 and V tile t+1 (tiles past the end read as zero)
-    auto fetch = [&](int t, int ks_slot, int vs_slot) __attribute__((always_inline)) {
-        ld.load(rk, ring_k + (uint32_t)ks_slot * TB, (t + 2) * KT, wave);
-        ld.load(rv, ring_v + (uint32_t)vs_slot * TB, (t + 1) * KT, wave);
-    };
-    // wait until only the newest fetch group of this wave is still in flight
-    auto wait_older = [&]() __attribute__((always_inline)) {
-        if (big_share) wait_vmem_le<2 * Loader::PER>();
-        else wait_vmem_le<2 * (Loader::PER - 1)>();
+    // fetch group issued at the start of an even period t: K tiles t+2, t+3 and V tiles
+    // t+1, t+2 (tiles past the end read as zero), into the slots that the two periods
+    // before the last barrier have left
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+        ld.load(rk, ring_k + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
+        ld.load(rv, ring_v + (uint32_t)((t + 1) & 3) * TB, (t + 1) * KT, wave);
+        ld.load(rk, ring_k + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
+        ld.load(rv, ring_v + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
     };
 
-    ld.load(rk, ring_k, 0, wave);  // K tile 0
-    fetch(-1, 1, 0);               // K tile 1, V tile 0
+    ld.load(rk, ring_k, 0, wave);            // K tile 0
+    ld.load(rk, ring_k + TB, KT, wave);      // K tile 1
+    ld.load(rv, ring_v, 0, wave);            // V tile 0
 
     {
         const uint16_t *qp =
@@ -336,32 +334,27 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     }
 
     // Period t: steps 2t-1 and 2t, i.e. S of both halves of K tile t and the
-    // O update with both halves of V tile t-1.  K tile t sits in slot t % 3,
-    // V tile t-1 in slot (t-1) % 3; the fetch of K tile t+2 / V tile t+1 goes to
-    // the slots that K tile t-1 / V tile t-2 left at the last barrier.
-    int kslot = 0, vslot = 2;  // slots of K tile t and V tile t-1
-    // start of a period: issue its fetch group; end: wait for the previous group, barrier, advance
+    // O update with both halves of V tile t-1.  K tile t sits in slot t % 4,
+    // V tile t-1 in slot (t-1) % 4.  Fetches are issued, and the workgroup meets at a
+    // barrier, every second period: an even period starts by fetching the tiles of the
+    // next two periods into the slots the previous two have left, an odd period ends
+    // with the wait for them and the barrier.
     auto period_begin = [&](int t) __attribute__((always_inline)) {
-        const int kslot_f = kslot == 0 ? 2 : kslot - 1;  // (t+2) % 3
-        const int vslot_f = vslot == 0 ? 2 : vslot - 1;  // (t+1) % 3
-        const bool more = t + 1 < n_tiles;  // V tile t+1 exists (K tile t+2 may read as zero)
-        if (more) fetch(t, kslot_f, vslot_f);
-        return more;
+        if ((t & 1) == 0 && t + 1 < n_tiles) fetch(t);  // V tile t+1 exists
     };
-    auto period_end = [&](bool more) __attribute__((always_inline)) {
-        if (more) wait_older();  // my share of K tile t+1 / V tile t has landed
-        else wait_vmem();        // nothing newer in flight
-        __syncthreads();         // ... and everyone's; everyone is done with K tile t / V tile t-1
-        kslot = kslot == 2 ? 0 : kslot + 1;
-        vslot = vslot == 2 ? 0 : vslot + 1;
+    auto period_end = [&](int t) __attribute__((always_inline)) {
+        if (t & 1) {
+            wait_vmem();      // my share of the next two periods' tiles has landed
+            __syncthreads();  // ... and everyone's; everyone is done with the last two periods' tiles
+        }
     };
     // periods whose two steps are fully inside the wave's unmasked range
     const int t_steady_end = min((L - 1) / 2, (n_full - 1) / 2);  // last t with 2t+1 <= L and 2t < n_full
     // one copy of the plain step, run for both halves of a period; its results
     // are moved back so that a period always starts from sx / px
     auto plain_period = [&](int t) __attribute__((always_inline)) {
-        const bool more = period_begin(t);
-        const unsigned char *tk = lds_k[kslot], *tv = lds_v[vslot];
+        period_begin(t);
+        const unsigned char *tk = lds_k[t & 3], *tv = lds_v[(t - 1) & 3];
 #pragma unroll 1
         for (int hh = 0; hh < 2; ++hh) {
             generic(2 * t - 1 + hh, tk + hh * HALF, tv + hh * HALF, sx, sy, px, py);
@@ -369,18 +362,18 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
             px[0] = py[0];
             px[1] = py[1];
         }
-        period_end(more);
+        period_end(t);
     };
     plain_period(0);
     int t = 1;
     // the pipelined loop proper: S and P ping-pong between two register sets
     for (; t <= t_steady_end; ++t) {
-        const bool more = period_begin(t);
-        const unsigned char *tk = lds_k[kslot], *tv = lds_v[vslot];
+        period_begin(t);
+        const unsigned char *tk = lds_k[t & 3], *tv = lds_v[(t - 1) & 3];
         bf16x8 kf[4], vf[4];  // operand fragments in flight
         steady(std::true_type{}, tk, tv, tk + HALF, tv + HALF, sx, sy, px, py, kf, vf);
         steady(std::false_type{}, tk + HALF, tv + HALF, tk, tv, sy, sx, py, px, kf, vf);
-        period_end(more);
+        period_end(t);
     }
 #pragma unroll 1
     for (; t <= n_tiles; ++t) plain_period(t);
