@@ -180,8 +180,11 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         float mx = fmaxf(s[0], s[1]);
 #pragma unroll
         for (int v = 2; v < 16; v += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[v]), s[v + 1]);
-        mx = max_halves(mx);
-        return fmaxf(m_run, mx * cs);
+        mx = max_halves(mx) * cs;
+        // The running maximum only has to bound the scores loosely: it moves when a
+        // score exceeds it by more than 2^8 (exponentials then stay below 256, far
+        // inside fp32 and bf16 range), so after the first tiles O is hardly ever rescaled.
+        return mx > m_run + 8.0f ? mx : m_run;
     };
     // rescale of the running sum and of O when some lane's maximum moved
     auto finish = [&](float m_new, float rs) __attribute__((always_inline)) {
