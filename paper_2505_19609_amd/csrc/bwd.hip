@@ -85,20 +85,60 @@ struct BwdParams {
 // ---------------------------------------------------------------------------
 // dQ
 // ---------------------------------------------------------------------------
-constexpr int NW = 4;          // wavefronts per workgroup
-constexpr int SUB = 32 * NW;   // query (dQ) or key (dK/dV) rows per pass
+constexpr int NW = 4;          // (dK/dV) pairs of waves per workgroup
+constexpr int SUB = 32 * NW;   // key rows per dK/dV pass
+constexpr int NWQ = 8;         // wavefronts of a dQ workgroup: 256 query rows, 32 per wave
 
-template <int D>
-__global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
+// Two scores and two (dP - D) values -> one packed bf16 pair of dS, in two parts so
+// that each part can sit behind one MFMA of a pipelined step (plain arithmetic would
+// be moved by the compiler to its first use, behind all the MFMAs of the step).
+// Part one: p = exp2(s * c - lse'); part two: p * (dP - D), packed.  Each exponential
+// has an instruction between it and the first use of its result.
+__device__ __forceinline__ void ds_exp2(float s0, float s1, float c, float l, float &t0, float &t1)
 {
-    constexpr int NT = 64 * NW, KS = D / 16, TT = D / 32, KT = TILE_ROWS;
-    constexpr int TILE_BYTES = TileGeom<D>::BYTES;
-    // Two [K rows | V rows] buffers, each its own LDS object, and a tile loop
-    // unrolled by two: every access names its buffer statically, so the compiler
-    // knows that operand reads never touch the buffer an asynchronous load is
-    // filling.  K and V share an object so that the V operand address is the K
-    // operand address plus a constant.
-    __shared__ __align__(16) unsigned char lds_kv0[2][TILE_BYTES], lds_kv1[2][TILE_BYTES];
+    asm volatile("v_fma_f32 %0, %2, %4, -%5\n\t"
+                 "v_fma_f32 %1, %3, %4, -%5\n\t"
+                 "v_exp_f32 %0, %0\n\t"
+                 "v_exp_f32 %1, %1"
+                 : "=&v"(t0), "=&v"(t1)
+                 : "v"(s0), "v"(s1), "s"(c), "v"(l));
+}
+__device__ __forceinline__ uint32_t ds_mul_pack(float t0, float t1, float g0, float g1)
+{
+    uint32_t pk;
+    float u0, u1;
+    asm volatile("v_mul_f32 %1, %3, %5\n\t"
+                 "v_mul_f32 %2, %4, %6\n\t"
+                 "v_cvt_pk_bf16_f32 %0, %1, %2"
+                 : "=&v"(pk), "=&v"(u0), "=&v"(u1)
+                 : "v"(t0), "v"(t1), "v"(g0), "v"(g1));
+    return pk;
+}
+
+// One workgroup = one forward work item (at most 256 query rows) x one query head;
+// each of the 8 waves owns 32 query rows, two waves per SIMD.  K and V stream in
+// 64-row tiles through LDS rings (K: five slots, V: four), fetched two tiles ahead by
+// buffer loads that write LDS directly; fetches are issued, and the workgroup meets
+// at a barrier, every second tile.  Half-tile j (32 keys) goes through
+//   A(j): S^T = K Q^T and dP^T - D = V dO^T with -D as the accumulator's start,
+//   V(j): dS^T = exp2(S^T c - LSE') (dP^T - D), rounded to bf16,
+//   B(j): dQ^T += K^T dS^T,
+// and step j issues A(j+1) with the vector work V(j) spread between its MFMAs, then
+// B(j).  B(j) reads the transposed K of the half tile BEFORE the one A(j+1) reads,
+// which is why the K ring has one slot more than the V ring.  Steps at the start, the
+// end and the causal diagonal of a wave's range take a plain path with guards.
+template <int D>
+__global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
+{
+    constexpr int KS = D / 16, TT = D / 32, KT = TILE_ROWS;
+    typedef TileGeom<D> G;
+    constexpr int TB = G::BYTES;
+    constexpr int HALF = 32 * G::ROWB;  // byte offset of a tile's second 32 rows
+    typedef RingLoader<D, NWQ> Loader;
+    static_assert(KS == 2 * TT, "B(j) has half as many MFMAs as A(j+1)");
+
+    __shared__ __align__(16) unsigned char lds_k[5][TB];
+    __shared__ __align__(16) unsigned char lds_v[4][TB];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
@@ -110,113 +150,233 @@ __global__ __launch_bounds__(64 * NW, 2) void dq_kernel(const BwdParams prm)
 
     FragAddr<D> fa;
     fa.init(lane);
-    TileLoader<D, NT> ld;
-    ld.init(tid, (uint32_t)prm.Hkv * D * 2);
+    Loader ld;
+    ld.init(lane, wave, (uint32_t)prm.Hkv * D * 2);
+    const uint32_t ring_k = lds_addr(&lds_k[0][0]), ring_v = lds_addr(&lds_v[0][0]);
 
     const int4 it = prm.fwd_items[item_id];
     const int seq = it.x;
     const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
     const int kbase = prm.cu_k[seq];
-    const int item_rows = min(prm.BM, ql - it.y * prm.BM);
-
-    for (int sub = 0; sub * SUB < item_rows; ++sub) {
-    const int row0 = it.y * prm.BM + sub * SUB;
-    const int qrow0 = it.z + sub * SUB;
-    const int rows = min(SUB, ql - row0);
-    const int p0 = qb + row0;
+    const int rows = min(prm.BM, ql - it.y * prm.BM);  // block_m <= 256: one pass per item
+    const int row0 = it.y * prm.BM;
+    const int qrow0 = it.z;
+    const int p0 = qb + row0;  // global position of the item's first query
     const int n_tiles = (p0 + rows + KT - 1) / KT;
+    const float cs = prm.scale_log2;
 
     const int wrow0 = 32 * wave;
     const bool wave_active = wrow0 < rows;
     const int my_i = wrow0 + n;
-    const int my_pos = p0 + my_i;
     const int w_pmin = p0 + wrow0;
     const int w_pmax = p0 + min(wrow0 + 31, rows - 1);
-    const int my_row = qrow0 + min(my_i, rows - 1);  // packed row, clamped for loads
+    // half tiles (32 keys) of this wave: 0..L hold a visible key, those below n_full only visible keys
+    const int L = wave_active ? w_pmax / 32 : -1;
+    const int n_full = wave_active ? (w_pmin + 1) / 32 : 0;
 
+    const i32x4 rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+    const i32x4 rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+
+    // fetch group issued at the start of an even period t: K and V tiles t+2, t+3
+    // (tiles past the end read as zero)
+    int kslot = 0;  // slot of K tile t (t mod 5), advanced at the end of every period
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+        const int k2 = kslot >= 3 ? kslot - 3 : kslot + 2, k3 = kslot >= 2 ? kslot - 2 : kslot + 3;
+        ld.load(rk, ring_k + (uint32_t)k2 * TB, (t + 2) * KT, wave);
+        ld.load(rv, ring_v + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
+        ld.load(rk, ring_k + (uint32_t)k3 * TB, (t + 3) * KT, wave);
+        ld.load(rv, ring_v + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
+    };
+    ld.load(rk, ring_k, 0, wave);
+    ld.load(rv, ring_v, 0, wave);
+    ld.load(rk, ring_k + TB, KT, wave);
+    ld.load(rv, ring_v + TB, KT, wave);
+
+    // B operands held for the whole item: this lane's query row of Q and dO
     bf16x8 qf[KS], dof[KS];
+    float lse2, nd;
     {
-        int hd = head;
-        asm volatile("" : "+s"(hd));  // keep this address arithmetic inside the pass
-        const size_t off = ((size_t)my_row * prm.Hq + hd) * D + 8 * h;
+        const int my_row = qrow0 + min(my_i, rows - 1);  // packed row, clamped for loads
+        const size_t off = ((size_t)my_row * prm.Hq + head) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             qf[ks] = as_bf16x8(*(const uint4 *)(prm.q + off + 16 * ks));
             dof[ks] = as_bf16x8(*(const uint4 *)(prm.d_o + off + 16 * ks));
         }
+        lse2 = prm.lse2[(size_t)head * prm.total_q + my_row];
+        nd = prm.delta[(size_t)head * prm.total_q + my_row];  // the workspace holds -D
     }
-    const float lse2 = prm.lse2[(size_t)head * prm.total_q + my_row];
-    const float dlt = -prm.delta[(size_t)head * prm.total_q + my_row];  // the workspace holds -D
-
-    const __amdgpu_buffer_rsrc_t rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
-    const __amdgpu_buffer_rsrc_t rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
+    // Everything issued so far has to land here: the compiler's own count of
+    // outstanding loads must be zero before the loops, or the waits it places
+    // for these fragments would also wait for the tile fetches in flight.
+    wait_vmem();
+    __syncthreads();
 
     f32x16 acc[TT];
     zero_acc(acc);
-    const float cs = prm.scale_log2;
 
-    auto do_tile = [&](int tile, const unsigned char *tk, unsigned char *nxt) __attribute__((always_inline)) {
-        const int kv0 = tile * KT;
-        if (tile + 1 < n_tiles) {  // lands in the other buffer during the math below
-            ld.load(rk, nxt, kv0 + KT, tid);
-            ld.load(rv, nxt + TILE_BYTES, kv0 + KT, tid);
+    // ---- pipelined step j: A(j+1) from kp / vp with V(j) on s_in / g_in between its
+    // MFMAs, then B(j) on the transposed K at kt.  FIRST: first step of a period (reads
+    // its first operands itself and, at the end, those of the second step from kp2 / vp2);
+    // otherwise they are already in fr.
+    auto steady = [&](auto first_tag, const unsigned char *kp, const unsigned char *vp,
+                      const unsigned char *kt, const unsigned char *kp2, const unsigned char *vp2,
+                      const f32x16 &s_in, const f32x16 &g_in, f32x16 &s_out, f32x16 &g_out,
+                      bf16x8 (&fr)[4]) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        // operand stream of the step: 2*KS reads for A (K rows, V rows alternating), then 2*TT for B
+        auto operand = [&](int x) __attribute__((always_inline)) {
+            if (x < 2 * KS) return (x & 1) ? fa.rows(vp, 0, x >> 1) : fa.rows(kp, 0, x >> 1);
+            const int y = x - 2 * KS;
+            return fa.cols(kt, y % TT, y / TT);
+        };
+        if (FIRST) {
+#pragma unroll
+            for (int x = 0; x < 3; ++x) fr[x] = operand(x);
         }
-        if (wave_active && kv0 <= w_pmax) {
-            const bool diag = kv0 + KT - 1 > w_pmin;  // some key of the tile is past some query
-            // 32 keys at a time: S^T and dP^T stay in 32 registers.
-#pragma unroll 1
-            for (int jt = 0; jt < 2; ++jt) {
-                const unsigned char *th = tk + jt * (32 * TileGeom<D>::ROWB);  // this half's 32 keys
-                f32x16 s, dp;
+        SB();
+        uint32_t pw[8];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) { s[v] = 0.0f; dp[v] = 0.0f; }
+        for (int i = 0; i < KS; ++i) {
+            constexpr int EPS = 16 / KS;  // dS values per step of the loop (2 or 4)
+            float t[EPS];
+            if (i == 0) {
+                f32x16 z;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s = mfma32(fa.rows(th, 0, ks), qf[ks], s);
-                    dp = mfma32(fa.rows(th + TILE_BYTES, 0, ks), dof[ks], dp);
-                }
-                if (diag) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float p = fast_exp2(__builtin_fmaf(s[v], cs, -lse2));
-                        p = (kv0 + 32 * jt + acc_row(v, h) > my_pos) ? 0.0f : p;
-                        s[v] = p * (dp[v] - dlt);  // dS^T
-                    }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        s[v] = fast_exp2(__builtin_fmaf(s[v], cs, -lse2)) * (dp[v] - dlt);
-                }
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 ds = acc_to_b(s, kb);
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[tt] = mfma32(fa.cols(th, tt, kb), ds, acc[tt]);
-                }
+                for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                s_out = mfma32(fr[0], qf[0], z);
+            } else {
+                s_out = mfma32(fr[(2 * i) % 4], qf[i], s_out);
             }
+#pragma unroll
+            for (int e = 0; e < EPS; e += 2)
+                ds_exp2(s_in[EPS * i + e], s_in[EPS * i + e + 1], cs, lse2, t[e], t[e + 1]);
+            fr[(2 * i + 3) % 4] = operand(2 * i + 3);
+            SB();
+            if (i == 0) {
+                f32x16 z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = nd;
+                g_out = mfma32(fr[1], dof[0], z);
+            } else {
+                g_out = mfma32(fr[(2 * i + 1) % 4], dof[i], g_out);
+            }
+#pragma unroll
+            for (int e = 0; e < EPS; e += 2)
+                pw[(EPS * i + e) >> 1] = ds_mul_pack(t[e], t[e + 1], g_in[EPS * i + e], g_in[EPS * i + e + 1]);
+            fr[(2 * i + 4) % 4] = operand(2 * i + 4);
+            SB();
         }
-        wait_vmem();      // my share of the next tile has landed
-        __syncthreads();  // ... and everyone's; everyone is done reading this tile
+        const bf16x8 ds0 = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        const bf16x8 ds1 = as_bf16x8(make_uint4(pw[4], pw[5], pw[6], pw[7]));
+#pragma unroll
+        for (int y = 0; y < 2 * TT; ++y) {
+            acc[y % TT] = mfma32(fr[(2 * KS + y) % 4], y < TT ? ds0 : ds1, acc[y % TT]);
+            const int nx = y + 3;  // of this step's B stream, then of the next step's A stream
+            if (nx < 2 * TT) {
+                fr[(2 * KS + nx) % 4] = operand(2 * KS + nx);
+            } else if (FIRST) {
+                const int x = nx - 2 * TT;
+                fr[x] = (x & 1) ? fa.rows(vp2, 0, x >> 1) : fa.rows(kp2, 0, x >> 1);
+            }
+            SB();
+        }
     };
 
-    __syncthreads();  // the previous pass is done with both buffers
-    ld.load(rk, lds_kv0[0], 0, tid);
-    ld.load(rv, lds_kv0[1], 0, tid);
-    wait_vmem();
-    __syncthreads();
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        do_tile(tile, lds_kv0[0], lds_kv1[0]);
-        if (tile + 1 < n_tiles) do_tile(tile + 1, lds_kv1[0], lds_kv0[0]);
+    // ---- plain step j with run-time guards (start, end and diagonal of the wave's range)
+    auto generic = [&](int j, const unsigned char *kp, const unsigned char *vp, const unsigned char *kt,
+                       const f32x16 &s_in, const f32x16 &g_in, f32x16 &s_out, f32x16 &g_out)
+                       __attribute__((always_inline)) {
+        if (j + 1 <= L) {  // A(j+1)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { s_out[v] = 0.0f; g_out[v] = nd; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s_out = mfma32(fa.rows(kp, 0, ks), qf[ks], s_out);
+                g_out = mfma32(fa.rows(vp, 0, ks), dof[ks], g_out);
+                if (ks % 4 == 3) SB();
+            }
+        }
+        if (j >= 0 && j <= L) {  // V(j), B(j)
+            f32x16 ds;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ds[v] = fast_exp2(__builtin_fmaf(s_in[v], cs, -lse2)) * g_in[v];
+            if (j >= n_full) {  // half tile touches the diagonal for this wave
+                // relative position from an opaque copy of the lane index: the sixteen
+                // per-register thresholds are formed here rather than kept for the whole kernel
+                int li = lane;
+                asm volatile("" : "+v"(li));
+                const int rel = p0 + wrow0 + (li & 31) - 32 * j - 4 * (li >> 5);  // my_pos - 32j - 4h
+#pragma unroll
+                for (int v = 0; v < 16; ++v) ds[v] = (8 * (v >> 2) + (v & 3) > rel) ? 0.0f : ds[v];
+            }
+            SB();
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const bf16x8 b = acc_to_b(ds, kb);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(fa.cols(kt, tt, kb), b, acc[tt]);
+                SB();
+            }
+        }
+    };
+
+    f32x16 sx, sy, gx, gy;  // S and dP - D of the current / next half tile, ping-pong
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sx[v] = 0.0f; sy[v] = 0.0f; gx[v] = 0.0f; gy[v] = 0.0f; }
+
+    // Period t: steps 2t-1 and 2t, i.e. A of both halves of tile t (K and V rows), B of
+    // the second half of K tile t-1 and of the first half of K tile t.  K tile t sits in
+    // slot t mod 5, V tile t in slot t mod 4.  An even period starts by fetching the
+    // tiles of the next two periods into slots that the periods before the last barrier
+    // have left; an odd period ends with the wait for them and the barrier.
+    auto period_begin = [&](int t) __attribute__((always_inline)) {
+        if ((t & 1) == 0 && t + 2 < n_tiles) fetch(t);
+    };
+    auto period_end = [&](int t) __attribute__((always_inline)) {
+        if (t & 1) {
+            wait_vmem();      // my share of the next two periods' tiles has landed
+            __syncthreads();  // ... and everyone's; everyone is done with the tiles they replace
+        }
+        kslot = kslot == 4 ? 0 : kslot + 1;
+    };
+    // periods whose two steps are fully inside the wave's unmasked range
+    const int t_steady_end = min((L - 1) / 2, (n_full - 1) / 2);  // last t with 2t+1 <= L and 2t < n_full
+    auto plain_period = [&](int t) __attribute__((always_inline)) {
+        period_begin(t);
+        const unsigned char *tk = lds_k[kslot], *tv = lds_v[t & 3];
+        const unsigned char *tkp = lds_k[kslot == 0 ? 4 : kslot - 1] + HALF;  // second half of K tile t-1
+#pragma unroll 1
+        for (int hh = 0; hh < 2; ++hh) {
+            generic(2 * t - 1 + hh, tk + hh * HALF, tv + hh * HALF, hh ? tk : tkp, sx, gx, sy, gy);
+            sx = sy;
+            gx = gy;
+        }
+        period_end(t);
+    };
+    plain_period(0);
+    int t = 1;
+    for (; t <= t_steady_end; ++t) {
+        period_begin(t);
+        const unsigned char *tk = lds_k[kslot], *tv = lds_v[t & 3];
+        const unsigned char *tkp = lds_k[kslot == 0 ? 4 : kslot - 1] + HALF;
+        bf16x8 fr[4];  // operand fragments in flight
+        steady(std::true_type{}, tk, tv, tkp, tk + HALF, tv + HALF, sx, gx, sy, gy, fr);
+        steady(std::false_type{}, tk + HALF, tv + HALF, tk, tk, tv, sy, gy, sx, gx, fr);
+        period_end(t);
     }
-    if (wave_active && my_i < rows) {
+#pragma unroll 1
+    for (; t <= n_tiles; ++t) plain_period(t);
+
+    if (wave_active) {
         // derived after the loop from opaque copies, so that no part of the
         // output address is kept in registers during the loop
-        int row = qrow0 + my_i, hh = h;
-        asm volatile("" : "+v"(row), "+v"(hh));
-        store_rows_bf16<TT>(prm.dq + ((size_t)row * prm.Hq + head) * D, acc, prm.scale, hh);
+        int li = lane;
+        asm volatile("" : "+v"(li));
+        const int on = li & 31, oh = li >> 5, oi = wrow0 + on;
+        if (oi < rows)
+            store_rows_bf16<TT>(prm.dq + ((size_t)(qrow0 + oi) * prm.Hq + head) * D, acc, prm.scale, oh);
     }
-    }  // pass
 }
 
 // ---------------------------------------------------------------------------
@@ -698,7 +858,7 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const voi
         if (e != hipSuccess) return e;
     }
     if (ev) (void)hipEventRecord(ev[2], st);
-    dq_kernel<D><<<gq, 64 * NW, 0, st>>>(prm);
+    dq_kernel<D><<<gq, 64 * NWQ, 0, st>>>(prm);
     if (ev) (void)hipEventRecord(ev[3], st);
     return hipGetLastError();
 }
