@@ -7,8 +7,8 @@
 //   dK_j  = scale * sum_{h in group} sum_i dS_ij q_i
 //   dV_j  =         sum_{h in group} sum_i P_ij dO_i
 //
-// dQ kernel: work items and orientation of the forward kernel (query index on
-// the MFMA column, so LSE_i and D_i are per-lane scalars):
+// dQ kernel: work items, workgroup shape and orientation of the forward kernel
+// (query index on the MFMA column, so LSE_i and D_i are per-lane scalars):
 //     S^T = K Q^T, dP^T = V dO^T           A = K / V tile rows (LDS), B = Q / dO (registers)
 //     dQ^T[t,i] += sum_j K^T[t,j] dS^T[j,i] A = transposed K tile (LDS), B = dS^T (registers)
 // dK/dV kernel: one workgroup owns BN key rows of one KV head and walks over

@@ -1,12 +1,13 @@
 // Forward kernel: packed varlen causal attention for one micro-batch
-// (local sequences whole, distributed ones as a contiguous query shard against
+// (local sequences whole, distributed ones as this rank's query segments against
 // the gathered KV prefix -- paper Sec. 4.1).  This is the O(n^2) term of the
 // paper's cost model (App. B.2), the thing its scheduler balances.
 //
 // One workgroup = one work item (a block of BM query rows of one sequence) x
 // one query head.  It has 8 wavefronts (two per SIMD), each owning 32 query
-// rows, so it covers 256 rows per pass.  The key / value prefix is streamed in
-// tiles of 64 rows through two rings of three LDS slots.
+// rows, so it covers 256 rows.  The key / value prefix is streamed in tiles of
+// 64 rows through two rings of four LDS slots: two tiles are read while the next
+// two are fetched, and the workgroup meets at a barrier every second tile.
 //
 // Orientation (see mfma.h): every tile is computed TRANSPOSED so that the
 // query index is the MFMA column and therefore lane-local:
@@ -99,13 +100,6 @@ __device__ __forceinline__ uint32_t softmax_sum_pack(float t0, float t1, float &
                  : "=v"(pk), "+v"(ra), "+v"(rb)
                  : "v"(t0), "v"(t1));
     return pk;
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmem_le()
-{
-    static_assert(N >= 0 && N < 16, "immediate form");
-    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
 }
 
 template <int D>

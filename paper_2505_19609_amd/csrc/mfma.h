@@ -35,20 +35,5 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, b);
 }
 
-// Row index (0..15) of accumulator register v for a lane in half h, within its
-// 8-row group pair: the full row is 8*(v/4) + 4*h + (v%4).
-__device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
-
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ float xor32(float x)
-{
-    // exchange with the lane 32 away (the other half of the wavefront)
-    return __shfl_xor(x, 32, 64);
-}
-
-// bf16 bits of a float widened back, for loads of single values.
-__device__ __forceinline__ float bf16_bits_to_float(uint16_t b)
-{
-    return __builtin_bit_cast(float, (uint32_t)b << 16);
-}

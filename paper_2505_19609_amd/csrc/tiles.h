@@ -81,60 +81,13 @@ struct FragAddr {
     }
 };
 
-// Buffer resource over `bytes` bytes starting at `base` (wave-uniform).  Loads
-// beyond the end return zero, which is how rows past the end of a sequence are
-// handled (the kernels mask them anyway).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-
-// Asynchronous loader of 64-row tiles of one [rows, H, D] matrix restricted to
-// one head.  One instruction makes a wave fill 64 consecutive 16-byte LDS slots
-// (slot = M0 base + lane) from per-lane offsets, so the row permutation and the
-// padding are applied on the global side: the lane that fills slot P fetches
-// the chunk that belongs there (padding slots fetch a harmless duplicate).
-// Per-thread state is one byte offset per issued instruction, fixed for the
-// kernel; the tile's row offset goes into the scalar offset operand.
-template <int D, int NT>
-struct TileLoader {
-    typedef TileGeom<D> G;
-    static constexpr int PER = (G::SLOTS + NT - 1) / NT;
-    int voff[PER];
-    uint32_t pitch;  // bytes between consecutive rows in global memory
-
-    __device__ __forceinline__ void init(int tid, uint32_t row_pitch_bytes)
-    {
-        pitch = row_pitch_bytes;
-#pragma unroll
-        for (int x = 0; x < PER; ++x) {
-            const int P = x * NT + tid;
-            const int pos = P / G::SPR, c = P % G::SPR;
-            voff[x] = row_pos(pos) * (int)row_pitch_bytes + (c < G::CH ? c * 16 : 0);
-        }
-    }
-    // rsrc covers rows [0, valid_rows) of the matrix starting at row 0 of the sequence
-    __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const uint16_t *row0_head, int valid_rows) const
-    {
-        return make_rsrc(row0_head, (uint32_t)(valid_rows - 1) * pitch + D * 2);
-    }
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned char *lds, int first_row, int tid) const
-    {
-        typedef void __attribute__((address_space(3))) * lds_void_t;
-        const int wave_first = tid & ~63;
-        const int soff = first_row * (int)pitch;
-#pragma unroll
-        for (int x = 0; x < PER; ++x) {
-            if ((x + 1) * NT <= G::SLOTS || x * NT + tid < G::SLOTS)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_t)(lds + (x * NT + wave_first) * 16), 16,
-                                                         voff[x], soff, 0, 0);
-        }
-    }
-};
-
 // ---------------------------------------------------------------------------
-// The same asynchronous tile fetch with the two instructions written out
-// (M0 <- LDS address; buffer load to LDS).  The compiler does not see these as
+// Asynchronous fetch of 64-row tiles of one [rows, H, D] matrix restricted to one
+// head.  One instruction makes a wave fill 64 consecutive 16-byte LDS slots (slot =
+// M0 base + lane) from per-lane offsets, so the row permutation and the padding are
+// applied on the global side: the lane that fills slot P fetches the chunk that
+// belongs there (padding slots fetch a harmless duplicate).  The two instructions are
+// written out (M0 <- LDS address; buffer load to LDS).  The compiler does not see these as
 // writes to LDS, so operand reads of OTHER ring slots are not made to wait for
 // a fetch in flight, whichever slot a run-time index selects; the kernels order
 // a slot's fetch and its reads themselves (wait_vmem + workgroup barrier).
