@@ -368,3 +368,30 @@ def test_head_split_is_chosen_from_the_work_list():
         with pytest.raises(B.SkrullError):
             B.skrull_attn_plan(w2.seq_len, w2.shard_degree, w2.shard_index, 14, 2, 64, 0.125, head_split=bad)
     p2.destroy(); p3.destroy()
+
+
+def test_autograd_wrapper(oracle):
+    """loss.backward() through the torch.autograd wrapper gives the library's gradients."""
+    import torch
+    from paper_2505_19609_amd import binding as B
+    from paper_2505_19609_amd.autograd import skrull_attention
+    from gpu_util import to_dev
+
+    w = W.Workload("autograd", [300, 1000, 77], [1, 2, 1], [0, 1, 0], 4, 2, 64, 0.125, 321, shard_cut=[0, 1, 0])
+    plan = B.skrull_attn_plan(w.seq_len, w.shard_degree, w.shard_index, 4, 2, 64, w.softmax_scale,
+                              shard_cut=w.shard_cut)
+    vals = W.make_values(w, plan.total_q, plan.total_k)
+    dev = {n: to_dev(a) for n, a in vals.items()}
+    q, k, v = (dev[n].clone().requires_grad_(True) for n in ("q", "k", "v"))
+    o = skrull_attention(q, k, v, plan)
+    (o.float() * dev["do"].float()).sum().backward()
+    torch.cuda.synchronize()
+    f = widen(vals)
+    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index, w.shard_cut)
+    O, _ = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
+    dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
+    _report("O", o.detach().float().cpu().numpy(), O, TOL_O)
+    _report("dQ", q.grad.float().cpu().numpy(), dQ, TOL_G)
+    _report("dK", k.grad.float().cpu().numpy(), dK, TOL_G)
+    _report("dV", v.grad.float().cpu().numpy(), dV, TOL_G)
+    plan.destroy()
