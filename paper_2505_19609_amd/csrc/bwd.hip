@@ -537,164 +537,184 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
     wait_vmem();
     __syncthreads();
 
-    // The two roles run the same round structure (same fetches, same barriers)
-    // in separate loops, so that each keeps only its own values in registers.
     // Round T: ring slot T % 3 holds (head T % g, query tile n_qt - 1 - T / g): heads
     // innermost, query tiles from the end of the sequence down to the block's
     // diagonal.  Every workgroup of a sequence then starts at the same tile and the
     // ones running together walk the same tiles at the same time, which is what
-    // lets the XCD's L2 serve most of their fetches.  (cq = tile of round T,
-    // (nh, nq) = head and tile of round T+1, fetched into the next slot.)
+    // lets the XCD's L2 serve most of their fetches.
+    // A pair's LIVE rounds are a prefix of the sequence: the tiles whose last query still
+    // precedes the pair's first key are the lowest ones, walked last.  Each role runs its
+    // live rounds in ONE loop with ONE sequence of MFMAs (masks, where a tile needs them,
+    // only change scores before the exponentials), then idles through the rest with the
+    // fetches and barriers every wave must take part in.  With alternative MFMA paths
+    // inside one loop the compiler reconciled their register assignments with ~100
+    // register copies per round.
+    auto tile_live = [&](int t) __attribute__((always_inline)) {
+        return tile_qb(t) + tile_i0(t) + QT - 1 >= wj0;
+    };
+    int n_live = 0;  // live rounds of this pair
+    if (wave_active) {
+        int dead_tiles = 0;
+        if (n_qt_e > 0) {  // the early chunk's lowest tile may be dead; the late chunk's never is
+            if (!tile_live(0)) dead_tiles = 1;
+        } else {
+            while (dead_tiles < n_qt && !tile_live(dead_tiles)) ++dead_tiles;
+        }
+        n_live = (n_qt - dead_tiles) * g;
+    }
+    int nh = 1, nq = n_qt - 1, cq = n_qt - 1, slot = 0;  // cq: tile of this round; (nh, nq): head, tile of the next
+    if (nh == g) { nh = 0; --nq; }
+    // start of a round: fetch the next round's tile; end: wait, barrier, advance
+    auto round_begin = [&](int T) __attribute__((always_inline)) {
+        if (T + 1 < n_iter) fetch(nh, nq, slot == 2 ? 0 : slot + 1);
+    };
+    auto round_end = [&]() __attribute__((always_inline)) {
+        wait_vmem();      // my share of the next tile has landed
+        __syncthreads();  // ... and everyone's; P of this round is visible; the previous slot is free
+        slot = slot == 2 ? 0 : slot + 1;
+        cq = nq;
+        if (++nh == g) { nh = 0; --nq; }
+    };
+    int T = 0;
     if (role == 0) {
-        int nh = 1, nq = n_qt - 1, cq = n_qt - 1, slot = 0;
-        if (nh == g) { nh = 0; --nq; }
-        for (int T = 0; T <= n_iter; ++T) {
-            const int slot_next = slot == 2 ? 0 : slot + 1;
-            if (T + 1 < n_iter) fetch(nh, nq, slot_next);
+#pragma unroll 1
+        for (; T < n_live; ++T) {
+            round_begin(T);
             const unsigned char *cur = lds_ring[slot];
             const int i0 = tile_i0(cq);  // first query row of the tile inside its segment
             const int qb_t = tile_qb(cq), ql_t = tile_ql(cq);
-            // a tile is skipped when its last query still precedes this pair's first key
-            const bool act = T < n_iter && wave_active && qb_t + i0 + QT - 1 >= wj0;
-            if (act) {
-                const unsigned char *tq = cur, *tdo = cur + TB;
-                const float *t_lse = (const float *)(cur + 2 * TB);
-                unsigned char *px = lds_p[pw][T & 1][0];
-                // masked pairs: key past the query (causal) or query row past the end
-                const bool need_mask = (qb_t + i0 < wj0 + 31) || (i0 + QT > ql_t);
-                f32x16 s[2];
-                bf16x8 fr[4];
-                // S of the first 32 rows; operand reads run three MFMAs ahead
+            const unsigned char *tq = cur, *tdo = cur + TB;
+            const float *t_lse = (const float *)(cur + 2 * TB);
+            unsigned char *px = lds_p[pw][T & 1][0];
+            // masked pairs: key past the query (causal) or query row past the end
+            const bool need_mask = (qb_t + i0 < wj0 + 31) || (i0 + QT > ql_t);
+            // scores of masked pairs become -inf (probability 0) before the exponentials
+            auto mask_block = [&](f32x16 &sb, int b) __attribute__((always_inline)) {
+                int li = lane;
+                asm volatile("" : "+v"(li));  // thresholds formed here, not kept across rounds
+                const int row0 = i0 + 32 * b + 4 * (li >> 5);            // + 8*vb + e = query row
 #pragma unroll
-                for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tq, 0, x);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    if (ks == 0) {
-                        f32x16 z;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                        s[0] = mfma32(fr[0], bf[0], z);
-                    } else {
-                        s[0] = mfma32(fr[ks % 4], bf[ks], s[0]);
-                    }
-                    const int nx = ks + 3;
-                    fr[nx % 4] = nx < KS ? fa.rows(tq, 0, nx) : fa.rows(tq, 1, nx - KS);
-                    SB();
+                for (int v = 0; v < 16; ++v) {
+                    const int i = row0 + 8 * (v >> 2) + (v & 3);
+                    sb[v] = (wj0 + (li & 31) > qb_t + i || i >= ql_t) ? -INFINITY : sb[v];
                 }
-                if (!need_mask) {
-                    // S of the second 32 rows with the probabilities of the first behind its
-                    // MFMAs, then dV of the first with the probabilities of the second
-                    uint32_t w[2][8];
-                    bf16x8 ft[4];
+            };
+            f32x16 s[2];
+            bf16x8 fr[4];
+            // S of the first 32 rows; operand reads run three MFMAs ahead
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        if (ks == 0) {
-                            f32x16 z;
+            for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tq, 0, x);
 #pragma unroll
-                            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                            s[1] = mfma32(fr[(KS + 0) % 4], bf[0], z);
-                        } else {
-                            s[1] = mfma32(fr[(KS + ks) % 4], bf[ks], s[1]);
-                        }
-                        const int nx = ks + 3;
-                        if (nx < KS) fr[(KS + nx) % 4] = fa.rows(tq, 1, nx);
-                        if (KS == 8 ? (ks % 2 == 1) : true) {
-                            const int vb = KS == 8 ? ks / 2 : ks;
-                            const float4 l4 = *(const float4 *)(t_lse + 8 * vb + 4 * h);
-                            const float sv[4] = {s[0][4 * vb], s[0][4 * vb + 1], s[0][4 * vb + 2], s[0][4 * vb + 3]};
-                            p_quad(sv, cs, l4, w[0][2 * vb], w[0][2 * vb + 1]);
-                        }
-                        if (ks >= KS - 3) ft[(ks - (KS - 3))] = fa.cols(tdo, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
-                        SB();
-                    }
-                    const bf16x8 pb0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
-                    const bf16x8 pb1 = as_bf16x8(make_uint4(w[0][4], w[0][5], w[0][6], w[0][7]));
-                    *(bf16x8 *)(px + 0 * 1024 + lane * 16) = pb0;
-                    *(bf16x8 *)(px + 1 * 1024 + lane * 16) = pb1;
-                    // dV of rows 0..31 (2 x TT MFMAs); probabilities of rows 32..63 behind them
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == 0) {
+                    f32x16 z;
 #pragma unroll
-                    for (int m = 0; m < 2 * TT; ++m) {
-                        acc[m % TT] = mfma32(ft[m % 4], m < TT ? pb0 : pb1, acc[m % TT]);
-                        const int nx = m + 3;
-                        ft[nx % 4] = fa.cols(tdo, nx % TT, nx / TT);  // runs on into rows 32..63
-                        if (TT == 4 ? (m % 2 == 1) : true) {
-                            const int vb = TT == 4 ? m / 2 : m;
-                            const float4 l4 = *(const float4 *)(t_lse + 32 + 8 * vb + 4 * h);
-                            const float sv[4] = {s[1][4 * vb], s[1][4 * vb + 1], s[1][4 * vb + 2], s[1][4 * vb + 3]};
-                            p_quad(sv, cs, l4, w[1][2 * vb], w[1][2 * vb + 1]);
-                        }
-                        SB();
-                    }
-                    const bf16x8 pb2 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
-                    const bf16x8 pb3 = as_bf16x8(make_uint4(w[1][4], w[1][5], w[1][6], w[1][7]));
-                    *(bf16x8 *)(px + 2 * 1024 + lane * 16) = pb2;
-                    *(bf16x8 *)(px + 3 * 1024 + lane * 16) = pb3;
-                    // dV of rows 32..63
-#pragma unroll
-                    for (int m = 2 * TT; m < 4 * TT; ++m) {
-                        acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? pb2 : pb3, acc[m % TT]);
-                        const int nx = m + 3;
-                        if (nx < 4 * TT) ft[nx % 4] = fa.cols(tdo, nx % TT, nx / TT);
-                        SB();
-                    }
+                    for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                    s[0] = mfma32(fr[0], bf[0], z);
                 } else {
-                    // tiles on the causal diagonal or at the end of the sequence: plain order
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        if (ks == 0) {
-                            f32x16 z;
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                            s[1] = mfma32(fr[(KS + 0) % 4], bf[0], z);
-                        } else {
-                            s[1] = mfma32(fr[(KS + ks) % 4], bf[ks], s[1]);
-                        }
-                        const int nx = ks + 3;
-                        if (nx < KS) fr[(KS + nx) % 4] = fa.rows(tq, 1, nx);
-                        SB();
-                    }
-#pragma unroll
-                    for (int b = 0; b < 2; ++b) {
-#pragma unroll
-                        for (int vb = 0; vb < 4; ++vb) {
-                            const float4 l4 = *(const float4 *)(t_lse + 32 * b + 8 * vb + 4 * h);
-                            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const int i = i0 + 32 * b + 8 * vb + 4 * h + e;
-                                const float pv = fast_exp2(__builtin_fmaf(s[b][4 * vb + e], cs, -lv[e]));
-                                s[b][4 * vb + e] = (my_j > qb_t + i || i >= ql_t) ? 0.0f : pv;
-                            }
-                        }
-                    }
-                    SB();
-#pragma unroll
-                    for (int kbg = 0; kbg < 4; ++kbg) {
-                        const bf16x8 pb = acc_to_b(s[kbg >> 1], kbg & 1);
-                        *(bf16x8 *)(px + kbg * 1024 + lane * 16) = pb;
-#pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(fa.cols(tdo, tt, kbg), pb, acc[tt]);
-                        SB();
-                    }
+                    s[0] = mfma32(fr[ks % 4], bf[ks], s[0]);
                 }
+                const int nx = ks + 3;
+                fr[nx % 4] = nx < KS ? fa.rows(tq, 0, nx) : fa.rows(tq, 1, nx - KS);
+                SB();
             }
-            wait_vmem();      // my share of the next tile has landed
-            __syncthreads();  // ... and everyone's; P of this round is visible; the previous slot is free
-            slot = slot_next;
-            cq = nq;
-            if (++nh == g) { nh = 0; --nq; }
+            if (need_mask) mask_block(s[0], 0);
+            // S of the second 32 rows with the probabilities of the first behind its
+            // MFMAs, then dV of the first with the probabilities of the second
+            uint32_t w[2][8];
+            bf16x8 ft[4];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == 0) {
+                    f32x16 z;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                    s[1] = mfma32(fr[(KS + 0) % 4], bf[0], z);
+                } else {
+                    s[1] = mfma32(fr[(KS + ks) % 4], bf[ks], s[1]);
+                }
+                const int nx = ks + 3;
+                if (nx < KS) fr[(KS + nx) % 4] = fa.rows(tq, 1, nx);
+                if (KS == 8 ? (ks % 2 == 1) : true) {
+                    const int vb = KS == 8 ? ks / 2 : ks;
+                    const float4 l4 = *(const float4 *)(t_lse + 8 * vb + 4 * h);
+                    const float sv[4] = {s[0][4 * vb], s[0][4 * vb + 1], s[0][4 * vb + 2], s[0][4 * vb + 3]};
+                    p_quad(sv, cs, l4, w[0][2 * vb], w[0][2 * vb + 1]);
+                }
+                if (ks >= KS - 3) ft[(ks - (KS - 3))] = fa.cols(tdo, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
+                SB();
+            }
+            if (need_mask) mask_block(s[1], 1);
+            const bf16x8 pb0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
+            const bf16x8 pb1 = as_bf16x8(make_uint4(w[0][4], w[0][5], w[0][6], w[0][7]));
+            *(bf16x8 *)(px + 0 * 1024 + lane * 16) = pb0;
+            *(bf16x8 *)(px + 1 * 1024 + lane * 16) = pb1;
+            // dV of rows 0..31 (2 x TT MFMAs); probabilities of rows 32..63 behind them
+#pragma unroll
+            for (int m = 0; m < 2 * TT; ++m) {
+                acc[m % TT] = mfma32(ft[m % 4], m < TT ? pb0 : pb1, acc[m % TT]);
+                const int nx = m + 3;
+                ft[nx % 4] = fa.cols(tdo, nx % TT, nx / TT);  // runs on into rows 32..63
+                if (TT == 4 ? (m % 2 == 1) : true) {
+                    const int vb = TT == 4 ? m / 2 : m;
+                    const float4 l4 = *(const float4 *)(t_lse + 32 + 8 * vb + 4 * h);
+                    const float sv[4] = {s[1][4 * vb], s[1][4 * vb + 1], s[1][4 * vb + 2], s[1][4 * vb + 3]};
+                    p_quad(sv, cs, l4, w[1][2 * vb], w[1][2 * vb + 1]);
+                }
+                SB();
+            }
+            const bf16x8 pb2 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
+            const bf16x8 pb3 = as_bf16x8(make_uint4(w[1][4], w[1][5], w[1][6], w[1][7]));
+            *(bf16x8 *)(px + 2 * 1024 + lane * 16) = pb2;
+            *(bf16x8 *)(px + 3 * 1024 + lane * 16) = pb3;
+            // dV of rows 32..63
+#pragma unroll
+            for (int m = 2 * TT; m < 4 * TT; ++m) {
+                acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? pb2 : pb3, acc[m % TT]);
+                const int nx = m + 3;
+                if (nx < 4 * TT) ft[nx % 4] = fa.cols(tdo, nx % TT, nx / TT);
+                SB();
+            }
+            round_end();
         }
     } else {
         f32x16 dp[2];  // dP - D of the previous round's tile
         zero_acc(dp);
-        bool prev_act = false;
-        int nh = 1, nq = n_qt - 1, cq = n_qt - 1, slot = 0;
-        if (nh == g) { nh = 0; --nq; }
-        for (int T = 0; T <= n_iter; ++T) {  // the extra round finishes the last tile
-            const int slot_next = slot == 2 ? 0 : slot + 1, slot_prev = slot == 0 ? 2 : slot - 1;
-            if (T + 1 < n_iter) fetch(nh, nq, slot_next);
+        // first live round: dP - D of its tile only
+        if (n_live > 0) {
+            round_begin(T);
+            const unsigned char *cur = lds_ring[slot];
+            const unsigned char *tdo = cur + TB;
+            const float *t_nd = (const float *)(cur + 2 * TB) + QT;  // -D of this round's tile
+            // accumulator start of a 32-row block of dP: -D of its rows
+            auto neg_d = [&](int b) __attribute__((always_inline)) {
+                f32x16 z;
+#pragma unroll
+                for (int vb = 0; vb < 4; ++vb) {
+                    const float4 d4 = *(const float4 *)(t_nd + 32 * b + 8 * vb + 4 * h);
+                    z[4 * vb] = d4.x; z[4 * vb + 1] = d4.y; z[4 * vb + 2] = d4.z; z[4 * vb + 3] = d4.w;
+                }
+                return z;
+            };
+            {
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    dp[b] = neg_d(b);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        dp[b] = mfma32(fa.rows(tdo, b, ks), bf[ks], dp[b]);
+                        if (ks % 4 == 3) SB();
+                    }
+                }
+            }
+            round_end();
+            ++T;
+        }
+#pragma unroll 1
+        for (; T < n_live; ++T) {
+            round_begin(T);
+            const int slot_prev = slot == 0 ? 2 : slot - 1;
             const unsigned char *cur = lds_ring[slot], *prv = lds_ring[slot_prev];
-            const bool act = T < n_iter && wave_active && tile_qb(cq) + tile_i0(cq) + QT - 1 >= wj0;
             const unsigned char *tdo = cur + TB;
             const float *t_nd = (const float *)(cur + 2 * TB) + QT;  // -D of this round's tile
             const unsigned char *pp = lds_p[pw][(T - 1) & 1][0];
@@ -715,93 +735,96 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
                 ds_quad(p4.x, p4.y, g0, w[0], w[1]);
                 ds_quad(p4.z, p4.w, g1, w[2], w[3]);
             };
-            if (act && prev_act) {
-                // Both tiles live: dP of this tile's first 32 rows with dS of the previous
-                // tile's first 32 rows behind its MFMAs; dK of those rows with the second dS
-                // behind; then dK of the second rows and dP of this tile's second rows.
-                f32x16 dpn;
-                bf16x8 fr[4], ft[4];
-                uint32_t w[4][4];
-                const uint4 p0 = *(const uint4 *)(pp + 0 * 1024 + lane * 16);
-                const uint4 p1 = *(const uint4 *)(pp + 1 * 1024 + lane * 16);
+            // Both tiles live: dP of this tile's first 32 rows with dS of the previous
+            // tile's first 32 rows behind its MFMAs; dK of those rows with the second dS
+            // behind; then dK of the second rows and dP of this tile's second rows.
+            f32x16 dpn;
+            bf16x8 fr[4], ft[4];
+            uint32_t w[4][4];
+            const uint4 p0 = *(const uint4 *)(pp + 0 * 1024 + lane * 16);
+            const uint4 p1 = *(const uint4 *)(pp + 1 * 1024 + lane * 16);
 #pragma unroll
-                for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 0, x);
-                dpn = neg_d(0);
+            for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 0, x);
+            dpn = neg_d(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    dpn = mfma32(fr[ks % 4], bf[ks], dpn);
-                    const int nx = ks + 3;
-                    if (nx < KS) fr[nx % 4] = fa.rows(tdo, 0, nx);
-                    if (ks == (KS == 8 ? 1 : 0)) ds_half(p0, dp[0], 0, w[0]);
-                    if (ks == (KS == 8 ? 4 : 2)) ds_half(p1, dp[0], 1, w[1]);
-                    if (ks >= KS - 3) ft[ks - (KS - 3)] = fa.cols(prv, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
+            for (int ks = 0; ks < KS; ++ks) {
+                dpn = mfma32(fr[ks % 4], bf[ks], dpn);
+                const int nx = ks + 3;
+                if (nx < KS) fr[nx % 4] = fa.rows(tdo, 0, nx);
+                if (ks == (KS == 8 ? 1 : 0)) ds_half(p0, dp[0], 0, w[0]);
+                if (ks == (KS == 8 ? 4 : 2)) ds_half(p1, dp[0], 1, w[1]);
+                if (ks >= KS - 3) ft[ks - (KS - 3)] = fa.cols(prv, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
+                SB();
+            }
+            const uint4 p2 = *(const uint4 *)(pp + 2 * 1024 + lane * 16);
+            const uint4 p3 = *(const uint4 *)(pp + 3 * 1024 + lane * 16);
+            const bf16x8 db0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
+            const bf16x8 db1 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
+#pragma unroll
+            for (int m = 0; m < 2 * TT; ++m) {
+                acc[m % TT] = mfma32(ft[m % 4], m < TT ? db0 : db1, acc[m % TT]);
+                const int nx = m + 3;
+                ft[nx % 4] = fa.cols(prv, nx % TT, nx / TT);  // runs on into rows 32..63
+                if (m == (TT == 4 ? 1 : 0)) ds_half(p2, dp[1], 0, w[2]);
+                if (m == (TT == 4 ? 4 : 2)) ds_half(p3, dp[1], 1, w[3]);
+                SB();
+            }
+            const bf16x8 db2 = as_bf16x8(make_uint4(w[2][0], w[2][1], w[2][2], w[2][3]));
+            const bf16x8 db3 = as_bf16x8(make_uint4(w[3][0], w[3][1], w[3][2], w[3][3]));
+#pragma unroll
+            for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 1, x);
+#pragma unroll
+            for (int m = 2 * TT; m < 4 * TT; ++m) {
+                acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? db2 : db3, acc[m % TT]);
+                const int nx = m + 3;
+                if (nx < 4 * TT) ft[nx % 4] = fa.cols(prv, nx % TT, nx / TT);
+                SB();
+            }
+            dp[0] = dpn;
+            dp[1] = neg_d(1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                dp[1] = mfma32(fr[ks % 4], bf[ks], dp[1]);
+                const int nx = ks + 3;
+                if (nx < KS) fr[nx % 4] = fa.rows(tdo, 1, nx);
+                SB();
+            }
+            round_end();
+        }
+        // the round after the last live one: dS and dK of the last live tile
+        if (n_live > 0) {
+            round_begin(T);
+            const int slot_prev = slot == 0 ? 2 : slot - 1;
+            const unsigned char *prv = lds_ring[slot_prev];
+            const unsigned char *pp = lds_p[pw][(T - 1) & 1][0];
+            // dS of 16 rows (block b, half kb) of the previous tile from its P and dP - D
+            auto ds_half = [&](const uint4 &p4, const f32x16 &g, int kb, uint32_t (&w)[4]) __attribute__((always_inline)) {
+                const float g0[4] = {g[8 * kb], g[8 * kb + 1], g[8 * kb + 2], g[8 * kb + 3]};
+                const float g1[4] = {g[8 * kb + 4], g[8 * kb + 5], g[8 * kb + 6], g[8 * kb + 7]};
+                ds_quad(p4.x, p4.y, g0, w[0], w[1]);
+                ds_quad(p4.z, p4.w, g1, w[2], w[3]);
+            };
+            {
+#pragma unroll
+                for (int kbg = 0; kbg < 4; ++kbg) {
+                    const uint4 p4 = *(const uint4 *)(pp + kbg * 1024 + lane * 16);
+                    uint32_t w[4];
+                    ds_half(p4, dp[kbg >> 1], kbg & 1, w);
+                    const bf16x8 db = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(fa.cols(prv, tt, kbg), db, acc[tt]);
                     SB();
-                }
-                const uint4 p2 = *(const uint4 *)(pp + 2 * 1024 + lane * 16);
-                const uint4 p3 = *(const uint4 *)(pp + 3 * 1024 + lane * 16);
-                const bf16x8 db0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
-                const bf16x8 db1 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
-#pragma unroll
-                for (int m = 0; m < 2 * TT; ++m) {
-                    acc[m % TT] = mfma32(ft[m % 4], m < TT ? db0 : db1, acc[m % TT]);
-                    const int nx = m + 3;
-                    ft[nx % 4] = fa.cols(prv, nx % TT, nx / TT);  // runs on into rows 32..63
-                    if (m == (TT == 4 ? 1 : 0)) ds_half(p2, dp[1], 0, w[2]);
-                    if (m == (TT == 4 ? 4 : 2)) ds_half(p3, dp[1], 1, w[3]);
-                    SB();
-                }
-                const bf16x8 db2 = as_bf16x8(make_uint4(w[2][0], w[2][1], w[2][2], w[2][3]));
-                const bf16x8 db3 = as_bf16x8(make_uint4(w[3][0], w[3][1], w[3][2], w[3][3]));
-#pragma unroll
-                for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 1, x);
-#pragma unroll
-                for (int m = 2 * TT; m < 4 * TT; ++m) {
-                    acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? db2 : db3, acc[m % TT]);
-                    const int nx = m + 3;
-                    if (nx < 4 * TT) ft[nx % 4] = fa.cols(prv, nx % TT, nx / TT);
-                    SB();
-                }
-                dp[0] = dpn;
-                dp[1] = neg_d(1);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    dp[1] = mfma32(fr[ks % 4], bf[ks], dp[1]);
-                    const int nx = ks + 3;
-                    if (nx < KS) fr[nx % 4] = fa.rows(tdo, 1, nx);
-                    SB();
-                }
-            } else {
-                if (prev_act) {  // dS and dK of the previous tile only (this tile is skipped, or the last round)
-#pragma unroll
-                    for (int kbg = 0; kbg < 4; ++kbg) {
-                        const uint4 p4 = *(const uint4 *)(pp + kbg * 1024 + lane * 16);
-                        uint32_t w[4];
-                        ds_half(p4, dp[kbg >> 1], kbg & 1, w);
-                        const bf16x8 db = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
-#pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) acc[tt] = mfma32(fa.cols(prv, tt, kbg), db, acc[tt]);
-                        SB();
-                    }
-                }
-                if (act) {  // dP - D of this tile only (first round, or the previous tile was skipped)
-#pragma unroll
-                    for (int b = 0; b < 2; ++b) {
-                        dp[b] = neg_d(b);
-#pragma unroll
-                        for (int ks = 0; ks < KS; ++ks) {
-                            dp[b] = mfma32(fa.rows(tdo, b, ks), bf[ks], dp[b]);
-                            if (ks % 4 == 3) SB();
-                        }
-                    }
                 }
             }
-            prev_act = act;
-            wait_vmem();
-            __syncthreads();
-            slot = slot_next;
-            cq = nq;
-            if (++nh == g) { nh = 0; --nq; }
+            round_end();
+            ++T;
         }
+    }
+    // rounds without work for this pair: keep fetching and meeting the others
+#pragma unroll 1
+    for (; T <= n_iter; ++T) {
+        round_begin(T);
+        round_end();
     }
     if (wave_active && my_j < kvl) {
         const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
