@@ -590,6 +590,8 @@ __global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
             const bool need_mask = (qb_t + i0 < wj0 + 31) || (i0 + QT > ql_t);
             // scores of masked pairs become -inf (probability 0) before the exponentials
             auto mask_block = [&](f32x16 &sb, int b) __attribute__((always_inline)) {
+                // (the asm also keeps this block behind its branch: turned into selects it
+                // would run in every round)
                 int li = lane;
                 asm volatile("" : "+v"(li));  // thresholds formed here, not kept across rounds
                 const int row0 = i0 + 32 * b + 4 * (li >> 5);            // + 8*vb + e = query row
