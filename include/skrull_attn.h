@@ -207,6 +207,15 @@ const char *skrull_attn_strerror(int code);
 int skrull_attn_profile(int enable);
 int skrull_attn_profile_read(float ms[4]);
 
+/*
+ * Measurement aid (not part of the method).  Runs three launches of about 20 ms of
+ * nothing but v_mfma_f32_32x32x16_bf16 on every compute unit (two waves per SIMD,
+ * operands in registers) on `hip_stream`, waits, and returns the rate of the last in TFLOP/s: the
+ * matrix-pipe ceiling this GPU sustains at the clock it holds under such load, to
+ * be read beside the nominal 2.5 PFLOP/s.  Allocates and frees a small scratch buffer.
+ */
+int skrull_attn_mfma_ceiling(void *hip_stream, float *tflops);
+
 #ifdef __cplusplus
 }
 #endif

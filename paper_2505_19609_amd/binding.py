@@ -20,6 +20,7 @@ CUT_CONTIGUOUS, CUT_TWO_CHUNKS = 0, 1
 EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
                     "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_plan_destroy",
                     "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read",
+                    "skrull_attn_mfma_ceiling",
                     "skrull_dacp_schedule", "skrull_dacp_rank_batch",
                     "skrull_gds_binpack", "skrull_gds_schedule", "skrull_gds_micro_batch")
 
@@ -95,6 +96,8 @@ def lib():
         L.skrull_attn_profile.restype = ctypes.c_int
         L.skrull_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
         L.skrull_attn_profile_read.restype = ctypes.c_int
+        L.skrull_attn_mfma_ceiling.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.skrull_attn_mfma_ceiling.restype = ctypes.c_int
         i32p = ctypes.POINTER(ctypes.c_int32)
         L.skrull_dacp_schedule.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32,
                                            ctypes.POINTER(FlopsModel), i32p]
@@ -214,6 +217,13 @@ def skrull_attn_profile_read():
     ms = (ctypes.c_float * 4)()
     _check(lib().skrull_attn_profile_read(ms))
     return [float(x) for x in ms]
+
+
+def skrull_attn_mfma_ceiling(stream=None) -> float:
+    """TFLOP/s this GPU sustains on bf16 MFMAs alone (measurement aid)."""
+    out = ctypes.c_float(0.0)
+    _check(lib().skrull_attn_mfma_ceiling(_stream_ptr(stream), ctypes.byref(out)))
+    return float(out.value)
 
 
 def skrull_dacp_schedule(seq_len, bucket_size, cp_degree, hidden, hidden_kv, batch=1) -> np.ndarray:

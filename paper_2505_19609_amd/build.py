@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libskrull_attn.so")
-SOURCES = ["api.hip", "plan.hip", "fwd.hip", "bwd.hip", "dacp.cpp", "gds.cpp"]
+SOURCES = ["api.hip", "plan.hip", "fwd.hip", "bwd.hip", "probe.hip", "dacp.cpp", "gds.cpp"]
 # packed fp32 VALU ops are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

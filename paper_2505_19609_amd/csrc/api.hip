@@ -278,6 +278,24 @@ void skrull_attn_plan_destroy(skrull_attn_plan_t *plan)
     delete plan;
 }
 
+int skrull_attn_mfma_ceiling(void *hip_stream, float *tflops)
+{
+    if (!tflops) return SKRULL_EINVAL;
+    int dev = 0, compute_units = 0;
+    int rc = check_device(&dev, &compute_units);
+    if (rc != SKRULL_OK) return rc;
+    const int blocks = compute_units, iters = 40000;  // ~20 ms of MFMAs
+    float *scratch = nullptr, ms = 0.0f;
+    hipError_t e = hipMalloc((void **)&scratch, (size_t)blocks * 512 * sizeof(float));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(probe)");
+    e = run_mfma_probe(blocks, iters, scratch, (hipStream_t)hip_stream, &ms);
+    (void)hipFree(scratch);
+    if (e != hipSuccess) return hip_fail(e, "MFMA probe");
+    // blocks x 8 waves x iters x 4 MFMAs x 32*32*16*2 flop
+    *tflops = (float)((double)blocks * 8.0 * iters * 4.0 * 32768.0 / (ms * 1e-3) / 1e12);
+    return SKRULL_OK;
+}
+
 int skrull_attn_profile(int enable)
 {
     if (enable && !g_ev_made) {

@@ -51,3 +51,6 @@ hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k,
 hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,
                       const void *o, const float *lse, const void *d_o, void *dq, void *dk,
                       void *dv, float *delta, hipStream_t st, hipEvent_t *ev);
+
+// probe.hip
+hipError_t run_mfma_probe(int blocks, int iters, float *scratch, hipStream_t st, float *ms);
