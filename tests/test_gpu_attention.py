@@ -395,3 +395,12 @@ def test_autograd_wrapper(oracle):
     _report("dK", k.grad.float().cpu().numpy(), dK, TOL_G)
     _report("dV", v.grad.float().cpu().numpy(), dV, TOL_G)
     plan.destroy()
+
+
+def test_mfma_ceiling_probe():
+    """The measurement aid returns a rate between a third of and just above the nominal
+    2.5 PFLOP/s (it is a pure MFMA loop at whatever clock the GPU holds)."""
+    from paper_2505_19609_amd import binding as B
+    rate = B.skrull_attn_mfma_ceiling()
+    print(f"MFMA-only ceiling: {rate:.0f} TFLOP/s")
+    assert 800.0 < rate < 2600.0
