@@ -133,7 +133,11 @@ extern "C" int skrull_gds_micro_batch(int32_t num_seqs, const int32_t *seq_len,
     int32_t n = 0;
     for (int32_t k = 0; k < num_seqs; ++k)
         if (micro_batch[k] == index) members[n++] = k;
-    std::stable_sort(members, members + n, [&](int32_t a, int32_t b) { return seq_len[a] < seq_len[b]; });
+    try {
+        std::stable_sort(members, members + n, [&](int32_t a, int32_t b) { return seq_len[a] < seq_len[b]; });
+    } catch (const std::bad_alloc &) {
+        return SKRULL_ENOMEM;
+    }
     *count = n;
     return SKRULL_OK;
 }
