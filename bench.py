@@ -170,8 +170,8 @@ def main():
                 "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                 "traffic": measured_traffic(w.name, dom),
                 "mfma_only_measured": round(ceiling, 1), "frac_of_measured": round(ach / ceiling, 4),
-                "kernel_ms": {"fwd": round(float(kms[0]), 4), "delta": round(float(kms[1]), 4),
-                              "dkv": round(float(kms[2]), 4), "dq": round(float(kms[3]), 4)}}
+                "kernel_ms": {"fwd": round(float(kms[0]), 4), "dkv": round(float(kms[2]), 4),
+                              "dq": round(float(kms[3]), 4)}}
     out = {
         "metric": "varlen causal attn fwd+bwd useful TFLOP/s, 1 GPU",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,

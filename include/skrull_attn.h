@@ -200,7 +200,8 @@ const char *skrull_attn_strerror(int code);
  * skrull_attn_bwd bracket each of their kernels with HIP events recorded on
  * the caller's stream.  skrull_attn_profile_read waits for the events of the
  * most recent forward and backward calls and returns the kernel durations in
- * milliseconds: ms[0] forward, ms[1] D = rowsum(dO*O), ms[2] dK/dV, ms[3] dQ
+ * milliseconds: ms[0] forward, ms[1] always 0 (D = rowsum(dO*O) is formed inside
+ * the dQ kernel), ms[2] dK/dV with its reduction, ms[3] dQ
  * (an entry is -1 if that call has not been made since enabling).  One set of
  * events per process: use from one thread, one stream at a time.
  */

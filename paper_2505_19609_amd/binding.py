@@ -213,7 +213,8 @@ def skrull_attn_profile(enable: bool):
 
 
 def skrull_attn_profile_read():
-    """Kernel durations (ms) of the last forward / backward: [fwd, delta, dkv, dq]."""
+    """Kernel durations (ms) of the last forward / backward: [fwd, 0, dkv, dq] (the second
+    slot was a separate rowsum(dO*O) kernel; the dQ kernel forms it now)."""
     ms = (ctypes.c_float * 4)()
     _check(lib().skrull_attn_profile_read(ms))
     return [float(x) for x in ms]

@@ -320,10 +320,11 @@ int skrull_attn_profile_read(float ms[4])
         if ((e = hipEventElapsedTime(&ms[0], g_ev[0], g_ev[1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
     }
     if (g_bwd_seen) {
-        if ((e = hipEventSynchronize(g_ev[5])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
-        for (int i = 0; i < 3; ++i)
-            if ((e = hipEventElapsedTime(&ms[1 + i], g_ev[2 + i], g_ev[3 + i])) != hipSuccess)
-                return hip_fail(e, "hipEventElapsedTime");
+        // backward events: g_ev[2] start, g_ev[3] after dQ (which also forms D), g_ev[4] after dK/dV
+        if ((e = hipEventSynchronize(g_ev[4])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        ms[1] = 0.0f;
+        if ((e = hipEventElapsedTime(&ms[3], g_ev[2], g_ev[3])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        if ((e = hipEventElapsedTime(&ms[2], g_ev[3], g_ev[4])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
     }
     return SKRULL_OK;
 }

@@ -30,46 +30,10 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// ---------------------------------------------------------------------------
-// D[h, row] = sum_t dO[row,h,t] * O[row,h,t]
-// ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void delta_kernel(const uint16_t *__restrict__ o,
-                                                    const uint16_t *__restrict__ d_o,
-                                                    const float *__restrict__ lse,
-                                                    float *__restrict__ delta,
-                                                    float *__restrict__ lse2, int64_t n_pairs,
-                                                    int32_t Hq, int32_t total_q)
-{
-    constexpr int CH = D / 8;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t pair = gid / CH;  // (row, head) flattened row-major
-    float acc = 0.0f;
-    if (pair < n_pairs) {
-        const uint4 a = *(const uint4 *)(o + gid * 8);
-        const uint4 b = *(const uint4 *)(d_o + gid * 8);
-        const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            acc += __builtin_bit_cast(float, aw[w] << 16) * __builtin_bit_cast(float, bw[w] << 16);
-            acc += __builtin_bit_cast(float, aw[w] & 0xffff0000u) *
-                   __builtin_bit_cast(float, bw[w] & 0xffff0000u);
-        }
-    }
-#pragma unroll
-    for (int off = CH / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (pair < n_pairs && (gid % CH) == 0) {
-        const int64_t row = pair / Hq;
-        const int32_t hh = (int32_t)(pair % Hq);
-        delta[(int64_t)hh * total_q + row] = -acc;  // the kernels add it (dP - D as dP + (-D))
-        // LSE in the exp2 domain, so the main kernels need no extra multiply
-        lse2[(int64_t)hh * total_q + row] = lse[(int64_t)hh * total_q + row] * kLog2e;
-    }
-}
-
 struct BwdParams {
-    const uint16_t *q, *k, *v, *d_o;
-    const float *lse, *delta, *lse2;
+    const uint16_t *q, *k, *v, *d_o, *o;
+    const float *lse;
+    float *delta, *lse2;  // workspace [Hq, total_q] each: -D and LSE * log2(e), written by the dQ kernel
     uint16_t *dq, *dk, *dv;
     const int4 *fwd_items, *dkv_items;
     const int32_t *cu_q, *cu_k, *q_begin, *q_len, *kv_len, *shares_kv;
@@ -203,8 +167,27 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
             qf[ks] = as_bf16x8(*(const uint4 *)(prm.q + off + 16 * ks));
             dof[ks] = as_bf16x8(*(const uint4 *)(prm.d_o + off + 16 * ks));
         }
-        lse2 = prm.lse2[(size_t)head * prm.total_q + my_row];
-        nd = prm.delta[(size_t)head * prm.total_q + my_row];  // the workspace holds -D
+        // D = rowsum(dO * O) of this lane's row (each half of the wave holds half of the
+        // head dims) and LSE in the exp2 domain; the dK/dV kernel, launched after this one,
+        // reads both from the workspace (it takes -D as the start of its dP accumulator)
+        float dsum = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint4 ow = *(const uint4 *)(prm.o + off + 16 * ks);
+            const uint4 gw = __builtin_bit_cast(uint4, dof[ks]);
+            const uint32_t a[4] = {ow.x, ow.y, ow.z, ow.w}, b[4] = {gw.x, gw.y, gw.z, gw.w};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                dsum += __builtin_bit_cast(float, a[w] << 16) * __builtin_bit_cast(float, b[w] << 16);
+                dsum += __builtin_bit_cast(float, a[w] & 0xffff0000u) * __builtin_bit_cast(float, b[w] & 0xffff0000u);
+            }
+        }
+        nd = -add_other_half(dsum);
+        lse2 = prm.lse[(size_t)head * prm.total_q + my_row] * kLog2e;
+        if (h == 0 && my_i < rows) {
+            prm.delta[(size_t)head * prm.total_q + my_row] = nd;
+            prm.lse2[(size_t)head * prm.total_q + my_row] = lse2;
+        }
     }
     // Everything issued so far has to land here: the compiler's own count of
     // outstanding loads must be zero before the loops, or the waits it places
@@ -858,19 +841,17 @@ __global__ __launch_bounds__(256) void dkv_reduce_kernel(const float *__restrict
 }
 
 template <int D>
-hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const void *o, float *delta,
-                    hipStream_t st, hipEvent_t *ev)
+hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream_t st, hipEvent_t *ev)
 {
+    // dQ first: it also leaves -D and LSE*log2(e) of every (head, row) in the workspace,
+    // which dK/dV reads.  Events: ev[0] start, ev[1] after dQ, ev[2] after dK/dV.
     if (ev) (void)hipEventRecord(ev[0], st);
-    const int64_t n_pairs = (int64_t)p->total_q * p->Hq;
-    const int64_t threads = n_pairs * (D / 8);
-    delta_kernel<D><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(
-        (const uint16_t *)o, prm.d_o, prm.lse, delta, (float *)prm.lse2, n_pairs, p->Hq, p->total_q);
+    const int gq = p->n_fwd * p->Hq;
+    const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + SUB - 1) / SUB);
+    dq_kernel<D><<<gq, 64 * NWQ, 0, st>>>(prm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    const int gq = p->n_fwd * p->Hq;
-    const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + SUB - 1) / SUB);
     dkv_kernel<D><<<gk, 64 * NWP, 0, st>>>(prm);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -883,8 +864,6 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, const voi
         if (e != hipSuccess) return e;
     }
     if (ev) (void)hipEventRecord(ev[2], st);
-    dq_kernel<D><<<gq, 64 * NWQ, 0, st>>>(prm);
-    if (ev) (void)hipEventRecord(ev[3], st);
     return hipGetLastError();
 }
 
@@ -896,7 +875,7 @@ hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k,
 {
     BwdParams prm;
     prm.q = (const uint16_t *)q; prm.k = (const uint16_t *)k; prm.v = (const uint16_t *)v;
-    prm.d_o = (const uint16_t *)d_o; prm.lse = lse; prm.delta = delta;
+    prm.d_o = (const uint16_t *)d_o; prm.o = (const uint16_t *)o; prm.lse = lse; prm.delta = delta;
     prm.lse2 = delta + (size_t)p->Hq * p->total_q;
     prm.dq = (uint16_t *)dq; prm.dk = (uint16_t *)dk; prm.dv = (uint16_t *)dv;
     prm.fwd_items = (const int4 *)p->fwd_items; prm.dkv_items = (const int4 *)p->dkv_items;
@@ -911,7 +890,7 @@ hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k,
         prm.dk_part = (float *)((char *)delta + rows);
         prm.dv_part = prm.dk_part + (size_t)p->head_split * p->total_k * p->Hkv * p->d;
     }
-    if (p->d == 128) return launch_d<128>(p, prm, o, delta, st, ev);
-    if (p->d == 64) return launch_d<64>(p, prm, o, delta, st, ev);
+    if (p->d == 128) return launch_d<128>(p, prm, st, ev);
+    if (p->d == 64) return launch_d<64>(p, prm, st, ev);
     return hipErrorInvalidValue;
 }

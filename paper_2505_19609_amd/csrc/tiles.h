@@ -201,6 +201,17 @@ __device__ __forceinline__ void store_rows_f32(float *dst, const f32x16 (&acc)[T
                 make_float4(acc[tt][4 * vb + 0], acc[tt][4 * vb + 1], acc[tt][4 * vb + 2], acc[tt][4 * vb + 3]);
 }
 
+// x + (x of the lane 32 away).  Written out with the operands copied first: given one
+// value for both operands, the swap builtin returns its first result twice.
+__device__ __forceinline__ float add_other_half(float x)
+{
+    float r, t;
+    asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %2\n\ts_nop 1\n\t"
+                 "v_permlane32_swap_b32 %0, %1\n\tv_add_f32 %0, %0, %1"
+                 : "=&v"(r), "=&v"(t) : "v"(x));
+    return r;
+}
+
 template <int N>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[N])
 {
