@@ -136,7 +136,11 @@ enum {
  * [0, degree), more chunks than tokens (degree > S_k, or 2*degree > S_k for a
  * two-chunk cut), a cut other than the two above, head_split outside [0, Hq/Hkv], Hq % Hkv != 0, head_dim not 64/128, a block size
  * other than 0/64/128/256, scale not finite/positive, a total of 2^31 rows or
- * more, or more than 2^20 work items in either list.
+ * more, more than 2^20 work items in either list, or a sequence too long for
+ * the kernels' 32-bit tile offsets: (rows of this rank's longest chunk + 256)
+ * * Hq * d * 2 bytes and (S_k + 256) * Hkv * d * 2 bytes must both stay below
+ * 2^32 (32 query heads of 128: 524,031 query rows per chunk; 8 KV heads of
+ * 128: 2,096,895 tokens per sequence).
  */
 int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_attn_plan_t **out);
 

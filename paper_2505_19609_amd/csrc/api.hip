@@ -81,6 +81,8 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     // than its sequence), which sizes the allocations and the grids, so that the whole
     // plan is built with one copy in, one copy out and one synchronisation.
     int64_t n_seg = 0;  // query segments: a two-chunk cut contributes two
+    const int64_t q_row_bytes = (int64_t)p->num_q_heads * p->head_dim * 2;
+    const int64_t kv_row_bytes = (int64_t)p->num_kv_heads * p->head_dim * 2;
     int64_t cap_fwd = 0, cap_dkv = 0;
     for (int32_t k = 0; k < K; ++k) {
         const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
@@ -89,6 +91,14 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         if (s < 1 || n < 1 || r < 0 || r >= n || (int64_t)n * (1 + z) > s) return SKRULL_EINVAL;
         n_seg += 1 + z;
         const int64_t chunks = (int64_t)n * (1 + z), longest = (s + chunks - 1) / chunks;
+        // The kernels address a tile as a 32-bit byte offset from the first row of its
+        // query segment (rows of Hq*d bf16) or of its key/value prefix (rows of Hkv*d
+        // bf16), and prefetch up to four 64-row tiles past the end (those read as zero).
+        if ((longest + 256) * q_row_bytes > (int64_t)UINT32_MAX ||
+            ((int64_t)s + 256) * kv_row_bytes > (int64_t)UINT32_MAX) {
+            snprintf(g_err, sizeof g_err, "sequence %d is too long for 32-bit tile offsets", k);
+            return SKRULL_EINVAL;
+        }
         cap_fwd += (1 + z) * ((longest + BM - 1) / BM);
         cap_dkv += ((int64_t)s + BN - 1) / BN;
     }

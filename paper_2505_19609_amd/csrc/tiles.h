@@ -152,7 +152,7 @@ struct RingLoader {
     }
     __device__ __forceinline__ void load(i32x4 r, uint32_t lds, int first_row, int wave) const
     {
-        const int soff = first_row * (int)pitch;
+        const int soff = (int)((uint32_t)first_row * pitch);  // below 2^32: checked when the plan is made
 #pragma unroll
         for (int x = 0; x < PER; ++x)
             if (x * NWV + wave < GROUPS) dma_b128(r, lds + (x * NWV + wave) * 1024, voff[x], soff);

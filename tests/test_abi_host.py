@@ -47,6 +47,9 @@ def test_strerror(B):
     dict(num_q_heads=0), dict(num_kv_heads=0), dict(head_dim=96), dict(softmax_scale=0.0),
     dict(softmax_scale=float("nan")), dict(softmax_scale=float("inf")), dict(block_m=96),
     dict(block_m=32), dict(block_n=2048), dict(block_m=512),
+    # 32-bit tile offsets: (S + 256) * Hkv * d * 2 and (chunk + 256) * Hq * d * 2 must stay below 2^32
+    dict(seq_len=[2_096_896], num_q_heads=8, num_kv_heads=8, head_dim=128, shard_degree=[8], shard_index=[0]),
+    dict(seq_len=[524_032], num_q_heads=32, num_kv_heads=8, head_dim=128),
 ])
 def test_invalid_problems_return_einval_without_a_device(B, kw):
     args = dict(seq_len=[10], shard_degree=[1], shard_index=[0], num_q_heads=4, num_kv_heads=2,
@@ -55,6 +58,22 @@ def test_invalid_problems_return_einval_without_a_device(B, kw):
     with pytest.raises(B.SkrullError) as e:
         B.skrull_attn_plan(raw_stream=0, **args)
     assert e.value.code == B.SKRULL_EINVAL
+
+
+def test_longest_addressable_sequences_pass_the_entry_checks(B):
+    """One row under the 32-bit offset limits: the checks that need no device pass
+    (the call then stops at the missing GPU, or succeeds where there is one)."""
+    import torch
+    for kw in (dict(seq_len=[2_096_895], num_q_heads=8, num_kv_heads=8, head_dim=128, shard_degree=[8], shard_index=[0]),
+               dict(seq_len=[524_031], num_q_heads=32, num_kv_heads=8, head_dim=128, shard_degree=[1], shard_index=[0])):
+        args = dict(softmax_scale=0.125, block_m=0, block_n=0)
+        args.update(kw)
+        if torch.cuda.is_available():
+            B.skrull_attn_plan(**args).destroy()
+        else:
+            with pytest.raises(B.SkrullError) as e:
+                B.skrull_attn_plan(raw_stream=0, **args)
+            assert e.value.code == B.SKRULL_EUNSUPPORTED
 
 
 def test_null_arguments(B):

@@ -143,8 +143,8 @@ def test_sequence_order_permutes_outputs(oracle):
 # ---------------------------------------------------------------------------
 # full-size micro-batches: sampled oracle parity + size-independent properties
 # ---------------------------------------------------------------------------
-def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400):
-    out = run_library(w)
+def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400, vals=None, heads_per_row=None):
+    out = run_library(w, vals=vals)
     f = widen(out["vals"])
     desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
     Hq, Hkv, d = w.num_q_heads, w.num_kv_heads, w.head_dim
@@ -160,7 +160,9 @@ def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400):
             fixed = [0, 1, 31, 32, 63, 64, 127, 128, ql - 129, ql - 128, ql - 65, ql - 2, ql - 1]
             rows = np.unique(np.concatenate([np.array(fixed), rng.integers(0, ql, rows_per_long)]))
         for i in rows:
-            heads = np.arange(Hq) if ql <= exhaustive_below else np.arange(Hq)
+            heads = np.arange(Hq)
+            if ql > exhaustive_below and heads_per_row is not None:
+                heads = np.sort(rng.choice(Hq, heads_per_row, replace=False))
             es.append(np.full(len(heads), k)); eh.append(heads); ei.append(np.full(len(heads), i))
     ent = tuple(np.concatenate(x).astype(np.int32) for x in (es, eh, ei))
     prow = desc["cu_q"][ent[0]] + ent[2]
@@ -207,22 +209,29 @@ def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400):
     # --- properties that hold at any size, on ALL outputs ---
     for n in ("o", "lse", "dq", "dk", "dv"):
         assert np.isfinite(out[n]).all(), n
-    q64, k64, v64 = (f[n].astype(np.float64) for n in ("q", "k", "v"))
+    def dots(x, y):
+        """Per head: sum of x*y over rows and head dims, accumulated in fp64, and an
+        estimate of the sum of (x*y)^2 (from every st-th row when there are many)."""
+        st = max(1, x.shape[0] // 65536)
+        xs, ys = x[::st], y[::st]
+        return (np.einsum("ihd,ihd->h", x, y, dtype=np.float64),
+                st * np.einsum("ihd,ihd,ihd,ihd->h", xs, ys, xs, ys, dtype=np.float64))
+
     for k in range(desc["num_seqs"]):
         qs, qe = desc["cu_q"][k], desc["cu_q"][k + 1]
         ks, ke = desc["cu_k"][k], desc["cu_k"][k + 1]
+        per_group = lambda t: t.reshape(Hkv, g).sum(axis=1)  # noqa: E731  (query heads of one KV head are adjacent)
+        tq, tq2 = (per_group(t) for t in dots(out["dq"][qs:qe], f["q"][qs:qe]))
+        tk, tk2 = dots(out["dk"][ks:ke], f["k"][ks:ke])
+        tv, tv2 = dots(out["dv"][ks:ke], f["v"][ks:ke])
+        to, to2 = (per_group(t) for t in dots(out["o"][qs:qe], f["do"][qs:qe]))
         for c in range(Hkv):
-            hs = slice(c * g, (c + 1) * g)
-            tq = out["dq"][qs:qe, hs].astype(np.float64) * q64[qs:qe, hs]
-            tk = out["dk"][ks:ke, c].astype(np.float64) * k64[ks:ke, c]
             # scale invariance of q.k: sum_i dQ_i.Q_i == sum_j dK_j.K_j per (sequence, group)
-            noise = 2.0 ** -8 * np.sqrt((tq ** 2).sum() + (tk ** 2).sum())
-            assert abs(tq.sum() - tk.sum()) <= 8 * noise + 1e-3, (k, c, tq.sum(), tk.sum(), noise)
+            noise = 2.0 ** -8 * np.sqrt(tq2[c] + tk2[c])
+            assert abs(tq[c] - tk[c]) <= 8 * noise + 1e-3, (k, c, tq[c], tk[c], noise)
             # O = P V  =>  sum_j dV_j.V_j == sum_i dO_i.O_i
-            tv = out["dv"][ks:ke, c].astype(np.float64) * v64[ks:ke, c]
-            to = out["o"][qs:qe, hs].astype(np.float64) * f["do"][qs:qe, hs].astype(np.float64)
-            noise = 2.0 ** -8 * np.sqrt((tv ** 2).sum() + (to ** 2).sum())
-            assert abs(tv.sum() - to.sum()) <= 8 * noise + 1e-3, (k, c, tv.sum(), to.sum(), noise)
+            noise = 2.0 ** -8 * np.sqrt(tv2[c] + to2[c])
+            assert abs(tv[c] - to[c]) <= 8 * noise + 1e-3, (k, c, tv[c], to[c], noise)
     out["plan"].destroy()
 
 
@@ -240,6 +249,25 @@ def test_config4_shard0_sampled(oracle):
 
 def test_config5_qwen7b_sampled(oracle):
     _sampled(oracle, W.config(5), rows_per_long=24, window=128, seed=505)
+
+
+@pytest.mark.timeout(400)
+def test_byte_offsets_past_2_31_sampled(oracle):
+    """One 270,000-token sequence with 32 heads of 128 on both sides: rows of 8 KB, so
+    the kernels' 32-bit tile offsets into Q, dO, K and V pass 2^31 (at row 262,144) and
+    end near 2.2e9.  Values are drawn on the GPU (seeded) because the numpy generator
+    would take minutes for 4.4e9 numbers; the oracle gets the same bits."""
+    import torch
+    S, H, d = 270_000, 32, 128
+    w = W.Workload("long270k_mha", [S], [1], [0], H, H, d, d ** -0.5, 0)
+    gen = torch.Generator(device="cuda").manual_seed(2_700)
+    vals = {}
+    for n in ("q", "k", "v", "do"):
+        t = torch.randn((S, H, d), generator=gen, device="cuda", dtype=torch.float32).bfloat16()
+        vals[n] = t.view(torch.int16).cpu().numpy().view(np.uint16)
+        del t
+    torch.cuda.empty_cache()
+    _sampled(oracle, w, rows_per_long=4, window=128, seed=270, vals=vals, heads_per_row=3)
 
 
 def test_shards_sum_to_unsharded_at_full_length():
