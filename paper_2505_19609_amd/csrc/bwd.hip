@@ -151,10 +151,13 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
         ld.load(rk, ring_k + (uint32_t)k3 * TB, (t + 3) * KT, wave);
         ld.load(rv, ring_v + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
     };
+    // start-up: tiles 0 and 1 and, with them, the fetch group of period 0 (its slots are
+    // empty), so that a short sequence pays the fetch latency once
     ld.load(rk, ring_k, 0, wave);
     ld.load(rv, ring_v, 0, wave);
     ld.load(rk, ring_k + TB, KT, wave);
     ld.load(rv, ring_v + TB, KT, wave);
+    if (2 < n_tiles) fetch(0);
 
     // B operands held for the whole item: this lane's query row of Q and dO
     bf16x8 qf[KS], dof[KS];
@@ -314,7 +317,7 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     // tiles of the next two periods into slots that the periods before the last barrier
     // have left; an odd period ends with the wait for them and the barrier.
     auto period_begin = [&](int t) __attribute__((always_inline)) {
-        if ((t & 1) == 0 && t + 2 < n_tiles) fetch(t);
+        if ((t & 1) == 0 && t > 0 && t + 2 < n_tiles) fetch(t);  // period 0's group went out at start-up
     };
     auto period_end = [&](int t) __attribute__((always_inline)) {
         if (t & 1) {

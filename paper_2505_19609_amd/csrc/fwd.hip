@@ -43,12 +43,18 @@ struct FwdParams {
     const int4 *items;
     const int32_t *cu_k, *q_begin, *q_len, *kv_len;
     int32_t Hq, Hkv, total_q, BM;
+    int32_t variant;  // 0: 4 wavefronts, 128 rows per workgroup; 1: 8 wavefronts, 256 rows
     float scale_log2;  // softmax_scale * log2(e)
 };
 
-constexpr int NW = 8;          // wavefronts per workgroup
-constexpr int SUB = 32 * NW;   // query rows per workgroup (the largest block_m)
-constexpr int NSLOT = 4;  // ring slots per operand: two tiles being read, two being fetched
+// Two shapes of the one kernel.  Large: 8 wavefronts = 256 query rows per workgroup and
+// 4 ring slots per operand (two tiles being read, two being fetched; a barrier every
+// second tile); its 139 KB of LDS leave room for one workgroup per compute unit.  Small
+// (items of at most 128 rows): 4 wavefronts and 2 ring slots (fetch one tile ahead, a
+// barrier every tile), 70 KB, so that two workgroups share a compute unit and the start-up
+// and drain of one (most of the run time of a short sequence) hide behind the other.
+constexpr int NW_LARGE = 8, NSLOT_LARGE = 4;
+constexpr int NW_SMALL = 4, NSLOT_SMALL = 2;
 
 
 // max / sum of a value over the two halves of the wavefront (lanes l and l ^ 32)
@@ -102,9 +108,11 @@ __device__ __forceinline__ uint32_t softmax_sum_pack(float t0, float t1, float &
     return pk;
 }
 
-template <int D>
+template <int D, int NW, int NSLOT>
 __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 {
+    static_assert(NSLOT == 2 || NSLOT == 4, "ring logic below covers two and four slots");
+    constexpr int SM = NSLOT - 1;  // slot of tile t: t & SM
     constexpr int KS = D / 16;   // MFMA k-steps of Q.K^T
     constexpr int TT = D / 32;   // 32-row tiles of O^T
     static_assert(KT == TILE_ROWS, "staging helpers assume 64-row tiles");
@@ -124,7 +132,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     // blockIdx -> (item, head).  Consecutive blocks go to consecutive XCDs; the
     // heads of one KV group are Hkv blocks apart so that they share an XCD (and
     // its L2 copy of the K/V tiles) whenever Hkv divides 8 or is a multiple of it.
-    const int item_id = blockIdx.x / prm.Hq, hl = blockIdx.x % prm.Hq;
+    // an item of more rows than the workgroup covers is split over `subs` workgroups
+    const int subs = (prm.BM + 32 * NW - 1) / (32 * NW);
+    const int item_id = blockIdx.x / (prm.Hq * subs), sub = (blockIdx.x / prm.Hq) % subs;
+    const int hl = blockIdx.x % prm.Hq;
     const int g = prm.Hq / prm.Hkv;
     const int c = hl % prm.Hkv;
     const int head = c * g + hl / prm.Hkv;
@@ -142,10 +153,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const int item_rows = min(prm.BM, ql - it.y * prm.BM);
     const float cs = prm.scale_log2;
 
-    // block_m is at most 256 = the rows one workgroup covers: one pass per item
-    const int row0 = it.y * prm.BM;
-    const int qrow0 = it.z;
-    const int rows = item_rows;
+    const int row0 = it.y * prm.BM + sub * 32 * NW;
+    const int qrow0 = it.z + sub * 32 * NW;
+    const int rows = min(32 * NW, item_rows - sub * 32 * NW);
+    if (rows <= 0) return;  // the item ends before this part (the whole workgroup leaves)
     const int p0 = qb + row0;  // global position of the pass's first query
     const int n_tiles = (p0 + rows + KT - 1) / KT;
 
@@ -295,19 +306,32 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
         }
     };
 
-    // fetch group issued at the start of an even period t: K tiles t+2, t+3 and V tiles
-    // t+1, t+2 (tiles past the end read as zero), into the slots that the two periods
-    // before the last barrier have left
+    // Four slots: the fetch group issued at the start of an even period t is K tiles t+2,
+    // t+3 and V tiles t+1, t+2 (tiles past the end read as zero), into the slots that the
+    // two periods before the last barrier have left.  Two slots: every period t starts by
+    // fetching K tile t+1 and V tile t into the slots period t-1 has left.
     auto fetch = [&](int t) __attribute__((always_inline)) {
-        ld.load(rk, ring_k + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
-        ld.load(rv, ring_v + (uint32_t)((t + 1) & 3) * TB, (t + 1) * KT, wave);
-        ld.load(rk, ring_k + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
-        ld.load(rv, ring_v + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
+        if (NSLOT == 4) {
+            ld.load(rk, ring_k + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
+            ld.load(rv, ring_v + (uint32_t)((t + 1) & 3) * TB, (t + 1) * KT, wave);
+            ld.load(rk, ring_k + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
+            ld.load(rv, ring_v + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
+        } else {
+            ld.load(rk, ring_k + (uint32_t)((t + 1) & 1) * TB, (t + 1) * KT, wave);
+            ld.load(rv, ring_v + (uint32_t)(t & 1) * TB, t * KT, wave);
+        }
     };
 
-    ld.load(rk, ring_k, 0, wave);            // K tile 0
-    ld.load(rk, ring_k + TB, KT, wave);      // K tile 1
-    ld.load(rv, ring_v, 0, wave);            // V tile 0
+    // Start-up: the tiles of the first period and, with them, the fetch group of period 0
+    // (its slots are empty), so that a short sequence pays the fetch latency once.
+    ld.load(rk, ring_k, 0, wave);  // K tile 0
+    if (NSLOT == 4) {
+        ld.load(rk, ring_k + TB, KT, wave);  // K tile 1
+        ld.load(rv, ring_v, 0, wave);        // V tile 0
+        if (1 < n_tiles) fetch(0);
+    } else {
+        fetch(0);
+    }
 
     {
         const uint16_t *qp =
@@ -331,18 +355,24 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     }
 
     // Period t: steps 2t-1 and 2t, i.e. S of both halves of K tile t and the
-    // O update with both halves of V tile t-1.  K tile t sits in slot t % 4,
-    // V tile t-1 in slot (t-1) % 4.  Fetches are issued, and the workgroup meets at a
-    // barrier, every second period: an even period starts by fetching the tiles of the
-    // next two periods into the slots the previous two have left, an odd period ends
-    // with the wait for them and the barrier.
+    // O update with both halves of V tile t-1.  K tile t sits in slot t % NSLOT,
+    // V tile t-1 in slot (t-1) % NSLOT.  With four slots fetches are issued, and the
+    // workgroup meets at a barrier, every second period: an even period starts by fetching
+    // the tiles of the next two periods into the slots the previous two have left, an odd
+    // period ends with the wait for them and the barrier.  With two slots every period
+    // fetches for the next one and ends with the wait and the barrier.
     auto period_begin = [&](int t) __attribute__((always_inline)) {
-        if ((t & 1) == 0 && t + 1 < n_tiles) fetch(t);  // V tile t+1 exists
+        if (t == 0) return;  // issued at start-up
+        if (NSLOT == 4) {
+            if ((t & 1) == 0 && t + 1 < n_tiles) fetch(t);  // V tile t+1 exists
+        } else {
+            if (t < n_tiles) fetch(t);  // V tile t exists
+        }
     };
     auto period_end = [&](int t) __attribute__((always_inline)) {
-        if (t & 1) {
-            wait_vmem();      // my share of the next two periods' tiles has landed
-            __syncthreads();  // ... and everyone's; everyone is done with the last two periods' tiles
+        if (NSLOT == 2 || (t & 1)) {
+            wait_vmem();      // my share of the tiles of the next period(s) has landed
+            __syncthreads();  // ... and everyone's; everyone is done with the tiles they replace
         }
     };
     // periods whose two steps are fully inside the wave's unmasked range
@@ -351,7 +381,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     // are moved back so that a period always starts from sx / px
     auto plain_period = [&](int t) __attribute__((always_inline)) {
         period_begin(t);
-        const unsigned char *tk = lds_k[t & 3], *tv = lds_v[(t - 1) & 3];
+        const unsigned char *tk = lds_k[t & SM], *tv = lds_v[(t - 1) & SM];
 #pragma unroll 1
         for (int hh = 0; hh < 2; ++hh) {
             generic(2 * t - 1 + hh, tk + hh * HALF, tv + hh * HALF, sx, sy, px, py);
@@ -366,7 +396,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     // the pipelined loop proper: S and P ping-pong between two register sets
     for (; t <= t_steady_end; ++t) {
         period_begin(t);
-        const unsigned char *tk = lds_k[t & 3], *tv = lds_v[(t - 1) & 3];
+        const unsigned char *tk = lds_k[t & SM], *tv = lds_v[(t - 1) & SM];
         bf16x8 kf[4], vf[4];  // operand fragments in flight
         steady(std::true_type{}, tk, tv, tk + HALF, tv + HALF, sx, sy, px, py, kf, vf);
         steady(std::false_type{}, tk + HALF, tv + HALF, tk, tv, sy, sx, py, px, kf, vf);
@@ -395,7 +425,12 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
 template <int D>
 hipError_t launch_one(const FwdParams &prm, int grid, hipStream_t st)
 {
-    fwd_kernel<D><<<grid, 64 * NW, 0, st>>>(prm);
+    if (prm.variant == 0) {
+        const int subs = (prm.BM + 32 * NW_SMALL - 1) / (32 * NW_SMALL);
+        fwd_kernel<D, NW_SMALL, NSLOT_SMALL><<<grid * subs, 64 * NW_SMALL, 0, st>>>(prm);
+    } else {
+        fwd_kernel<D, NW_LARGE, NSLOT_LARGE><<<grid, 64 * NW_LARGE, 0, st>>>(prm);
+    }
     return hipGetLastError();
 }
 
@@ -412,6 +447,7 @@ hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM;
     prm.scale_log2 = p->scale * 1.4426950408889634f;
     const int grid = p->n_fwd * p->Hq;
+    prm.variant = p->forward_rows == 32 * NW_SMALL ? 0 : 1;
     if (p->d == 128) return launch_one<128>(prm, grid, st);
     if (p->d == 64) return launch_one<64>(prm, grid, st);
     return hipErrorInvalidValue;

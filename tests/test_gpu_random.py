@@ -1,5 +1,5 @@
 """Seeded random micro-batches (lengths, shard degrees and indices, both cuts, head
-counts, head_dim, block sizes, head split) against the fp64 oracle, exhaustively.
+counts, head_dim, block sizes, head split, forward workgroup shape) against the fp64 oracle, exhaustively.
 Every case is a valid problem; sizes are small enough for the oracle but span several
 tiles, ragged tails, one-token chunks and every code path of the kernels."""
 import numpy as np
@@ -36,15 +36,17 @@ def _case(seed):
     bm = int(rng.choice([0, 64, 128, 256]))
     bn = int(rng.choice([0, 64, 128, 256]))
     hs = int(rng.integers(0, g + 1))
-    return S, N, R, Z, Hkv * g, Hkv, d, bm, bn, hs
+    fr = int(rng.choice([0, 128, 256]))   # drawn last: the other parameters of a seed stay what they were
+    return S, N, R, Z, Hkv * g, Hkv, d, bm, bn, hs, fr
 
 
 @pytest.mark.parametrize("seed", range(48))
 def test_random_micro_batch(oracle, seed):
-    S, N, R, Z, Hq, Hkv, d, bm, bn, hs = _case(seed)
-    print(f"seed {seed}: S={S} N={N} R={R} cut={Z} heads={Hq}/{Hkv} d={d} bm={bm} bn={bn} head_split={hs}", flush=True)
+    S, N, R, Z, Hq, Hkv, d, bm, bn, hs, fr = _case(seed)
+    print(f"seed {seed}: S={S} N={N} R={R} cut={Z} heads={Hq}/{Hkv} d={d} bm={bm} bn={bn} head_split={hs} "
+          f"forward_rows={fr}", flush=True)
     w = W.Workload(f"rand{seed}", S, N, R, Hq, Hkv, d, d ** -0.5, 20_000 + seed, shard_cut=Z)
-    out = run_library(w, bm, bn, head_split=hs)
+    out = run_library(w, bm, bn, head_split=hs, forward_rows=fr)
     f = widen(out["vals"])
     desc = oracle.ranges(S, N, R, Z)
     O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
