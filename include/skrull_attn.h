@@ -63,7 +63,7 @@ typedef struct {
     int32_t        block_n;       /* key rows per dK/dV work item: 64, 128 or 256; 0 = 128      */
     const int32_t *shard_cut;     /* [K] HOST or NULL (= all SKRULL_CUT_CONTIGUOUS)             */
     int32_t        head_split;    /* dK/dV workgroups per KV group, 1..Hq/Hkv; 0 = library's choice */
-    int32_t        forward_rows;  /* query rows per forward workgroup: 128 or 256; 0 = library's choice */
+    int32_t        wg_query_rows; /* query rows per forward / dQ workgroup: 128 or 256; 0 = library's choice */
 } skrull_attn_problem_t;
 
 /*
@@ -96,7 +96,8 @@ typedef struct {
     int64_t bwd_workspace_bytes;  /* device scratch skrull_attn_bwd needs (>= 0)               */
     int32_t num_segments;         /* query segments: K + number of two-chunk sequences         */
     int32_t head_split;           /* the dK/dV head split in effect (>= 1)                     */
-    int32_t forward_rows;         /* query rows per forward workgroup in effect (128 or 256)   */
+    int32_t wg_query_rows;        /* query rows per forward / dQ workgroup in effect (128 or 256;
+                                     dQ has the 128-row shape at head_dim 64 only)             */
     int32_t reserved;             /* 0                                                         */
 } skrull_attn_plan_info_t;
 
@@ -138,7 +139,7 @@ enum {
  * SKRULL_EINVAL: null pointer, K < 1, S_k < 1, degree < 1, index outside
  * [0, degree), more chunks than tokens (degree > S_k, or 2*degree > S_k for a
  * two-chunk cut), a cut other than the two above, head_split outside [0, Hq/Hkv],
- * forward_rows other than 0/128/256, Hq % Hkv != 0, head_dim not 64/128, a block size
+ * wg_query_rows other than 0/128/256, Hq % Hkv != 0, head_dim not 64/128, a block size
  * other than 0/64/128/256, scale not finite/positive, a total of 2^31 rows or
  * more, more than 2^20 work items in either list, or a sequence too long for
  * the kernels' 32-bit tile offsets: (rows of this rank's longest chunk + 256)

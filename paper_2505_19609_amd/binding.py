@@ -37,7 +37,7 @@ class Problem(ctypes.Structure):
                 ("block_m", ctypes.c_int32),
                 ("block_n", ctypes.c_int32),
                 ("shard_cut", ctypes.POINTER(ctypes.c_int32)),
-                ("head_split", ctypes.c_int32), ("forward_rows", ctypes.c_int32)]
+                ("head_split", ctypes.c_int32), ("wg_query_rows", ctypes.c_int32)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -49,7 +49,7 @@ class PlanInfo(ctypes.Structure):
                 ("attended_pairs", ctypes.c_int64), ("useful_flops_fwd", ctypes.c_int64),
                 ("useful_flops_bwd", ctypes.c_int64), ("bwd_workspace_bytes", ctypes.c_int64),
                 ("num_segments", ctypes.c_int32), ("head_split", ctypes.c_int32),
-                ("forward_rows", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("wg_query_rows", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class FlopsModel(ctypes.Structure):
@@ -157,7 +157,7 @@ class Plan:
 
 def skrull_attn_plan(seq_len, shard_degree, shard_index, num_q_heads, num_kv_heads, head_dim,
                      softmax_scale, block_m=0, block_n=0, stream=None, raw_stream=None,
-                     shard_cut=None, head_split=0, forward_rows=0) -> Plan:
+                     shard_cut=None, head_split=0, wg_query_rows=0) -> Plan:
     S = np.ascontiguousarray(seq_len, dtype=np.int32)
     N = np.ascontiguousarray(shard_degree, dtype=np.int32)
     R = np.ascontiguousarray(shard_index, dtype=np.int32)
@@ -168,7 +168,7 @@ def skrull_attn_plan(seq_len, shard_degree, shard_index, num_q_heads, num_kv_hea
     prob = Problem(int(S.shape[0]), S.ctypes.data_as(i32p), N.ctypes.data_as(i32p),
                    R.ctypes.data_as(i32p), num_q_heads, num_kv_heads, head_dim,
                    float(softmax_scale), block_m, block_n,
-                   None if Z is None else Z.ctypes.data_as(i32p), int(head_split), int(forward_rows))
+                   None if Z is None else Z.ctypes.data_as(i32p), int(head_split), int(wg_query_rows))
     handle = ctypes.c_void_p()
     st = ctypes.c_void_p(raw_stream) if raw_stream is not None else _stream_ptr(stream)
     _check(lib().skrull_attn_plan(ctypes.byref(prob), st, ctypes.byref(handle)))

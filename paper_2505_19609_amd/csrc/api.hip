@@ -75,7 +75,7 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         return SKRULL_EINVAL;
     const int32_t group = p->num_q_heads / p->num_kv_heads;
     if (p->head_split < 0 || p->head_split > group) return SKRULL_EINVAL;
-    if (p->forward_rows != 0 && p->forward_rows != 128 && p->forward_rows != 256) return SKRULL_EINVAL;
+    if (p->wg_query_rows != 0 && p->wg_query_rows != 128 && p->wg_query_rows != 256) return SKRULL_EINVAL;
     // Entry checks are done here so that they work without a device; the kernel repeats
     // them next to the range computation.  The same pass bounds the number of work
     // items from above (chunk lengths differ by at most one row; a prefix is no longer
@@ -180,12 +180,14 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     // the compute units.  When the longest chain exceeds that share (few KV heads, one
     // long sequence in a small micro-batch) the heads of a group are shared out over
     // several workgroups until it no longer does, with a factor two of slack.
-    // Forward workgroup shape.  Two 4-wavefront workgroups per compute unit hide each
-    // other's start-up, drain and barriers: 8-21 % faster at head_dim 64 at every length
-    // measured (256 ... 65,536) and at head_dim 128 up to 4,096-token sequences, equal
-    // at 8,192, 1-2 % slower beyond, where the 8-wavefront workgroup's deeper tile ring
-    // and halved tile traffic win.
-    plan->forward_rows = p->forward_rows != 0 ? p->forward_rows
+    // Workgroup shape of the forward and dQ kernels.  Two 4-wavefront workgroups per
+    // compute unit hide each other's start-up, drain and barriers.  Forward: 8-21 % faster
+    // at head_dim 64 at every length measured (256 ... 65,536) and at head_dim 128 up to
+    // 4,096-token sequences, equal at 8,192, 1-2 % slower beyond, where the 8-wavefront
+    // workgroup's deeper tile ring and halved tile traffic win.  dQ: the small shape fits
+    // twice into the LDS only at head_dim 64; there it is 17 % (256 tokens) to 2 % (65,536)
+    // faster.
+    plan->wg_query_rows = p->wg_query_rows != 0 ? p->wg_query_rows
                          : (p->head_dim == 64 || longest_seq <= 8192) ? 128 : 256;
     plan->head_split = p->head_split;
     if (plan->head_split == 0) {
@@ -234,7 +236,7 @@ int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_
         info->bwd_workspace_bytes += 2 * (int64_t)plan->head_split * plan->total_k * plan->Hkv * plan->d * 4;
     info->num_segments = plan->NS;
     info->head_split = plan->head_split;
-    info->forward_rows = plan->forward_rows;
+    info->wg_query_rows = plan->wg_query_rows;
     info->reserved = 0;
     return SKRULL_OK;
 }

@@ -51,7 +51,11 @@ struct BwdParams {
 // ---------------------------------------------------------------------------
 constexpr int NW = 4;          // (dK/dV) pairs of waves per workgroup
 constexpr int SUB = 32 * NW;   // key rows per dK/dV pass
-constexpr int NWQ = 8;         // wavefronts of a dQ workgroup: 256 query rows, 32 per wave
+// The dQ kernel comes in two shapes, like the forward: 8 wavefronts (256 query rows) with a
+// five-slot K ring and a four-slot V ring, one workgroup per compute unit; and, where two of
+// them fit the LDS together (head_dim 64), 4 wavefronts (128 rows) with three K slots and two
+// V slots, fetching one tile ahead with a barrier per tile.
+constexpr int NWQ_LARGE = 8, NWQ_SMALL = 4;
 
 // Two scores and two (dP - D) values -> one packed bf16 pair of dS, in two parts so
 // that each part can sit behind one MFMA of a pipelined step (plain arithmetic would
@@ -91,9 +95,11 @@ __device__ __forceinline__ uint32_t ds_mul_pack(float t0, float t1, float g0, fl
 // B(j).  B(j) reads the transposed K of the half tile BEFORE the one A(j+1) reads,
 // which is why the K ring has one slot more than the V ring.  Steps at the start, the
 // end and the causal diagonal of a wave's range take a plain path with guards.
-template <int D>
+template <int D, int NWQ>
 __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
 {
+    constexpr bool SMALL = NWQ == NWQ_SMALL;
+    constexpr int KSL = SMALL ? 3 : 5, VSL = SMALL ? 2 : 4;  // ring slots
     constexpr int KS = D / 16, TT = D / 32, KT = TILE_ROWS;
     typedef TileGeom<D> G;
     constexpr int TB = G::BYTES;
@@ -101,13 +107,16 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     typedef RingLoader<D, NWQ> Loader;
     static_assert(KS == 2 * TT, "B(j) has half as many MFMAs as A(j+1)");
 
-    __shared__ __align__(16) unsigned char lds_k[5][TB];
-    __shared__ __align__(16) unsigned char lds_v[4][TB];
+    __shared__ __align__(16) unsigned char lds_k[KSL][TB];
+    __shared__ __align__(16) unsigned char lds_v[VSL][TB];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int n = lane & 31, h = lane >> 5;
-    const int item_id = blockIdx.x / prm.Hq, hl = blockIdx.x % prm.Hq;
+    // an item of more rows than the workgroup covers is split over `subs` workgroups
+    const int subs = (prm.BM + 32 * NWQ - 1) / (32 * NWQ);
+    const int item_id = blockIdx.x / (prm.Hq * subs), sub = (blockIdx.x / prm.Hq) % subs;
+    const int hl = blockIdx.x % prm.Hq;
     const int g = prm.Hq / prm.Hkv;
     const int c = hl % prm.Hkv;
     const int head = c * g + hl / prm.Hkv;
@@ -122,9 +131,10 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     const int seq = it.x;
     const int qb = prm.q_begin[seq], ql = prm.q_len[seq], kvl = prm.kv_len[seq];
     const int kbase = prm.cu_k[seq];
-    const int rows = min(prm.BM, ql - it.y * prm.BM);  // block_m <= 256: one pass per item
-    const int row0 = it.y * prm.BM;
-    const int qrow0 = it.z;
+    const int row0 = it.y * prm.BM + sub * 32 * NWQ;
+    const int qrow0 = it.z + sub * 32 * NWQ;
+    const int rows = min(32 * NWQ, min(prm.BM, ql - it.y * prm.BM) - sub * 32 * NWQ);
+    if (rows <= 0) return;  // the item ends before this part (the whole workgroup leaves)
     const int p0 = qb + row0;  // global position of the item's first query
     const int n_tiles = (p0 + rows + KT - 1) / KT;
     const float cs = prm.scale_log2;
@@ -141,23 +151,33 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     const i32x4 rk = ld.rsrc(prm.k + ((size_t)kbase * prm.Hkv + c) * D, kvl);
     const i32x4 rv = ld.rsrc(prm.v + ((size_t)kbase * prm.Hkv + c) * D, kvl);
 
-    // fetch group issued at the start of an even period t: K and V tiles t+2, t+3
-    // (tiles past the end read as zero)
-    int kslot = 0;  // slot of K tile t (t mod 5), advanced at the end of every period
+    // Large shape: the fetch group issued at the start of an even period t is K and V tiles
+    // t+2, t+3 (tiles past the end read as zero).  Small shape: every period t fetches K
+    // and V tile t+1.
+    int kslot = 0;  // slot of K tile t (t mod KSL), advanced at the end of every period
     auto fetch = [&](int t) __attribute__((always_inline)) {
-        const int k2 = kslot >= 3 ? kslot - 3 : kslot + 2, k3 = kslot >= 2 ? kslot - 2 : kslot + 3;
-        ld.load(rk, ring_k + (uint32_t)k2 * TB, (t + 2) * KT, wave);
-        ld.load(rv, ring_v + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
-        ld.load(rk, ring_k + (uint32_t)k3 * TB, (t + 3) * KT, wave);
-        ld.load(rv, ring_v + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
+        if (SMALL) {
+            ld.load(rk, ring_k + (uint32_t)(kslot == 2 ? 0 : kslot + 1) * TB, (t + 1) * KT, wave);
+            ld.load(rv, ring_v + (uint32_t)((t + 1) & 1) * TB, (t + 1) * KT, wave);
+        } else {
+            const int k2 = kslot >= 3 ? kslot - 3 : kslot + 2, k3 = kslot >= 2 ? kslot - 2 : kslot + 3;
+            ld.load(rk, ring_k + (uint32_t)k2 * TB, (t + 2) * KT, wave);
+            ld.load(rv, ring_v + (uint32_t)((t + 2) & 3) * TB, (t + 2) * KT, wave);
+            ld.load(rk, ring_k + (uint32_t)k3 * TB, (t + 3) * KT, wave);
+            ld.load(rv, ring_v + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
+        }
     };
-    // start-up: tiles 0 and 1 and, with them, the fetch group of period 0 (its slots are
-    // empty), so that a short sequence pays the fetch latency once
+    // start-up: the tiles of the first period(s) and, with them, the fetch group of period 0
+    // (its slots are empty), so that a short sequence pays the fetch latency once
     ld.load(rk, ring_k, 0, wave);
     ld.load(rv, ring_v, 0, wave);
-    ld.load(rk, ring_k + TB, KT, wave);
-    ld.load(rv, ring_v + TB, KT, wave);
-    if (2 < n_tiles) fetch(0);
+    if (SMALL) {
+        if (1 < n_tiles) fetch(0);
+    } else {
+        ld.load(rk, ring_k + TB, KT, wave);
+        ld.load(rv, ring_v + TB, KT, wave);
+        if (2 < n_tiles) fetch(0);
+    }
 
     // B operands held for the whole item: this lane's query row of Q and dO
     bf16x8 qf[KS], dof[KS];
@@ -313,25 +333,33 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
 
     // Period t: steps 2t-1 and 2t, i.e. A of both halves of tile t (K and V rows), B of
     // the second half of K tile t-1 and of the first half of K tile t.  K tile t sits in
-    // slot t mod 5, V tile t in slot t mod 4.  An even period starts by fetching the
-    // tiles of the next two periods into slots that the periods before the last barrier
-    // have left; an odd period ends with the wait for them and the barrier.
+    // slot t mod KSL, V tile t in slot t mod VSL.  Large shape: an even period starts by
+    // fetching the tiles of the next two periods into slots that the periods before the
+    // last barrier have left; an odd period ends with the wait for them and the barrier.
+    // Small shape: every period fetches the next tile (into the slot of K tile t-2, whose
+    // second half period t-1 was the last to read, and of V tile t-1) and ends with the
+    // wait and the barrier.
     auto period_begin = [&](int t) __attribute__((always_inline)) {
-        if ((t & 1) == 0 && t > 0 && t + 2 < n_tiles) fetch(t);  // period 0's group went out at start-up
+        if (t == 0) return;  // period 0's group went out at start-up
+        if (SMALL) {
+            if (t + 1 < n_tiles) fetch(t);
+        } else {
+            if ((t & 1) == 0 && t + 2 < n_tiles) fetch(t);
+        }
     };
     auto period_end = [&](int t) __attribute__((always_inline)) {
-        if (t & 1) {
-            wait_vmem();      // my share of the next two periods' tiles has landed
+        if (SMALL || (t & 1)) {
+            wait_vmem();      // my share of the tiles of the next period(s) has landed
             __syncthreads();  // ... and everyone's; everyone is done with the tiles they replace
         }
-        kslot = kslot == 4 ? 0 : kslot + 1;
+        kslot = kslot == KSL - 1 ? 0 : kslot + 1;
     };
     // periods whose two steps are fully inside the wave's unmasked range
     const int t_steady_end = min((L - 1) / 2, (n_full - 1) / 2);  // last t with 2t+1 <= L and 2t < n_full
     auto plain_period = [&](int t) __attribute__((always_inline)) {
         period_begin(t);
-        const unsigned char *tk = lds_k[kslot], *tv = lds_v[t & 3];
-        const unsigned char *tkp = lds_k[kslot == 0 ? 4 : kslot - 1] + HALF;  // second half of K tile t-1
+        const unsigned char *tk = lds_k[kslot], *tv = lds_v[t & (VSL - 1)];
+        const unsigned char *tkp = lds_k[kslot == 0 ? KSL - 1 : kslot - 1] + HALF;  // second half of K tile t-1
 #pragma unroll 1
         for (int hh = 0; hh < 2; ++hh) {
             generic(2 * t - 1 + hh, tk + hh * HALF, tv + hh * HALF, hh ? tk : tkp, sx, gx, sy, gy);
@@ -344,8 +372,8 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     int t = 1;
     for (; t <= t_steady_end; ++t) {
         period_begin(t);
-        const unsigned char *tk = lds_k[kslot], *tv = lds_v[t & 3];
-        const unsigned char *tkp = lds_k[kslot == 0 ? 4 : kslot - 1] + HALF;
+        const unsigned char *tk = lds_k[kslot], *tv = lds_v[t & (VSL - 1)];
+        const unsigned char *tkp = lds_k[kslot == 0 ? KSL - 1 : kslot - 1] + HALF;
         bf16x8 fr[4];  // operand fragments in flight
         steady(std::true_type{}, tk, tv, tkp, tk + HALF, tv + HALF, sx, gx, sy, gy, fr);
         steady(std::false_type{}, tk + HALF, tv + HALF, tk, tk, tv, sy, gy, sx, gx, fr);
@@ -851,7 +879,12 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream
     if (ev) (void)hipEventRecord(ev[0], st);
     const int gq = p->n_fwd * p->Hq;
     const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + SUB - 1) / SUB);
-    dq_kernel<D><<<gq, 64 * NWQ, 0, st>>>(prm);
+    if (D == 64 && p->wg_query_rows == 32 * NWQ_SMALL) {
+        const int subs = (p->BM + 32 * NWQ_SMALL - 1) / (32 * NWQ_SMALL);
+        dq_kernel<D, NWQ_SMALL><<<gq * subs, 64 * NWQ_SMALL, 0, st>>>(prm);
+    } else {
+        dq_kernel<D, NWQ_LARGE><<<gq, 64 * NWQ_LARGE, 0, st>>>(prm);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);

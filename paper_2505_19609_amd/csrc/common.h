@@ -14,7 +14,7 @@ struct skrull_attn_plan {
     int32_t total_q, total_k, n_fwd, n_dkv;
     int64_t pairs;
     int32_t head_split;  // workgroups that share the query heads of one KV group in dK/dV
-    int32_t forward_rows;  // query rows per forward workgroup: 128 (4 wavefronts) or 256 (8)
+    int32_t wg_query_rows;  // query rows per forward / dQ workgroup: 128 (4 wavefronts) or 256 (8)
     int device;
     // one allocation (descriptor arrays, then the two item lists); the pointers below index into it
     int32_t *pool;

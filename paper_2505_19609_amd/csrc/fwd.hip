@@ -447,7 +447,7 @@ hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM;
     prm.scale_log2 = p->scale * 1.4426950408889634f;
     const int grid = p->n_fwd * p->Hq;
-    prm.variant = p->forward_rows == 32 * NW_SMALL ? 0 : 1;
+    prm.variant = p->wg_query_rows == 32 * NW_SMALL ? 0 : 1;
     if (p->d == 128) return launch_one<128>(prm, grid, st);
     if (p->d == 64) return launch_one<64>(prm, grid, st);
     return hipErrorInvalidValue;

@@ -9,7 +9,7 @@ def to_dev(bits):
 
 
 def run_library(w, block_m=0, block_n=0, vals=None, backward=True, keep_device=False, head_split=0,
-                forward_rows=0):
+                wg_query_rows=0):
     """Plan + forward (+ backward) of workload ``w`` on the current GPU."""
     import torch
     from paper_2505_19609_amd import binding as B
@@ -17,7 +17,7 @@ def run_library(w, block_m=0, block_n=0, vals=None, backward=True, keep_device=F
 
     plan = B.skrull_attn_plan(w.seq_len, w.shard_degree, w.shard_index, w.num_q_heads,
                               w.num_kv_heads, w.head_dim, w.softmax_scale, block_m, block_n,
-                              shard_cut=w.shard_cut, head_split=head_split, forward_rows=forward_rows)
+                              shard_cut=w.shard_cut, head_split=head_split, wg_query_rows=wg_query_rows)
     if vals is None:
         vals = W.make_values(w, plan.total_q, plan.total_k)
     dev = {n: to_dev(a) for n, a in vals.items()}

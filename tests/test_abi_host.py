@@ -46,7 +46,7 @@ def test_strerror(B):
     dict(shard_index=[-1]), dict(seq_len=[3], shard_degree=[4]), dict(num_q_heads=6, num_kv_heads=4),
     dict(num_q_heads=0), dict(num_kv_heads=0), dict(head_dim=96), dict(softmax_scale=0.0),
     dict(softmax_scale=float("nan")), dict(softmax_scale=float("inf")), dict(block_m=96),
-    dict(block_m=32), dict(block_n=2048), dict(block_m=512), dict(forward_rows=64), dict(forward_rows=-1),
+    dict(block_m=32), dict(block_n=2048), dict(block_m=512), dict(wg_query_rows=64), dict(wg_query_rows=-1),
     # 32-bit tile offsets: (S + 256) * Hkv * d * 2 and (chunk + 256) * Hq * d * 2 must stay below 2^32
     dict(seq_len=[2_096_896], num_q_heads=8, num_kv_heads=8, head_dim=128, shard_degree=[8], shard_index=[0]),
     dict(seq_len=[524_032], num_q_heads=32, num_kv_heads=8, head_dim=128),

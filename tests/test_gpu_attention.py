@@ -30,8 +30,10 @@ def _report(name, got, ref, tol):
     return float(err[i])
 
 
-def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G, head_split=0):
-    out = run_library(w, block_m, block_n, head_split=head_split)
+def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G, head_split=0, wg_query_rows=0):
+    out = run_library(w, block_m, block_n, head_split=head_split, wg_query_rows=wg_query_rows)
+    if wg_query_rows:
+        assert out["plan"].info.wg_query_rows == wg_query_rows
     f = widen(out["vals"])
     desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index, w.shard_cut)
     O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
@@ -144,8 +146,8 @@ def test_sequence_order_permutes_outputs(oracle):
 # full-size micro-batches: sampled oracle parity + size-independent properties
 # ---------------------------------------------------------------------------
 def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400, vals=None, heads_per_row=None,
-             forward_rows=0):
-    out = run_library(w, vals=vals, forward_rows=forward_rows)
+             wg_query_rows=0):
+    out = run_library(w, vals=vals, wg_query_rows=wg_query_rows)
     f = widen(out["vals"])
     desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
     Hq, Hkv, d = w.num_q_heads, w.num_kv_heads, w.head_dim
@@ -253,8 +255,8 @@ def test_config5_qwen7b_sampled(oracle):
 
 
 @pytest.mark.timeout(400)
-@pytest.mark.parametrize("forward_rows", [128, 256])
-def test_byte_offsets_past_2_31_sampled(oracle, forward_rows):
+@pytest.mark.parametrize("wg_query_rows", [128, 256])
+def test_byte_offsets_past_2_31_sampled(oracle, wg_query_rows):
     """One 270,000-token sequence with 32 heads of 128 on both sides: rows of 8 KB, so
     the kernels' 32-bit tile offsets into Q, dO, K and V pass 2^31 (at row 262,144) and
     end near 2.2e9.  Values are drawn on the GPU (seeded) because the numpy generator
@@ -270,7 +272,7 @@ def test_byte_offsets_past_2_31_sampled(oracle, forward_rows):
         del t
     torch.cuda.empty_cache()
     _sampled(oracle, w, rows_per_long=4, window=128, seed=270, vals=vals, heads_per_row=3,
-             forward_rows=forward_rows)
+             wg_query_rows=wg_query_rows)
 
 
 def test_shards_sum_to_unsharded_at_full_length():
@@ -404,32 +406,25 @@ def test_head_split_is_chosen_from_the_work_list():
 @pytest.mark.parametrize("rows", [128, 256])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("bm", [0, 64])
-def test_forward_workgroup_shapes(oracle, rows, d, bm):
-    """Both shapes of the forward kernel (4 wavefronts x 128 rows with a two-slot tile
-    ring, 8 x 256 with four slots) on a micro-batch with one-tile, ragged and
-    many-tile sequences and a distributed slice."""
-    w = W.Workload(f"fwd_rows{rows}_d{d}", [1, 63, 129, 700, 1411, 2600], [1, 1, 1, 1, 1, 2],
+def test_workgroup_shapes(oracle, rows, d, bm):
+    """Both shapes of the forward and dQ kernels (4 wavefronts x 128 rows, fetching one tile
+    ahead, and 8 x 256 with the deeper tile rings) on a micro-batch with one-tile, ragged
+    and many-tile sequences and a distributed slice."""
+    w = W.Workload(f"wg_rows{rows}_d{d}", [1, 63, 129, 700, 1411, 2600], [1, 1, 1, 1, 1, 2],
                    [0, 0, 0, 0, 0, 1], 4, 2, d, d ** -0.5, 77)
-    out = run_library(w, block_m=bm, backward=False, forward_rows=rows)
-    assert out["plan"].info.forward_rows == rows
-    f = widen(out["vals"])
-    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
-    O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
-    _report("O", out["o"], O, TOL_O)
-    _report("LSE", out["lse"], LSE, TOL_O)
-    out["plan"].destroy()
+    _exhaustive(oracle, w, block_m=bm, wg_query_rows=rows)
 
 
-def test_forward_workgroup_shape_is_chosen_from_head_dim_and_length():
+def test_workgroup_shape_is_chosen_from_head_dim_and_length():
     from paper_2505_19609_amd import binding as B
     for S, d, want in (([8192, 100], 128, 128), ([8193, 100], 128, 256), ([65536], 64, 128),
                        ([131072], 128, 256), ([300], 128, 128)):
         n = [8 if s > 100000 else 1 for s in S]
         plan = B.skrull_attn_plan(S, n, [0] * len(S), 8, 2, d, d ** -0.5)
-        assert plan.info.forward_rows == want, (S, d)
+        assert plan.info.wg_query_rows == want, (S, d)
         plan.destroy()
-        plan = B.skrull_attn_plan(S, n, [0] * len(S), 8, 2, d, d ** -0.5, forward_rows=384 - want)
-        assert plan.info.forward_rows == 384 - want
+        plan = B.skrull_attn_plan(S, n, [0] * len(S), 8, 2, d, d ** -0.5, wg_query_rows=384 - want)
+        assert plan.info.wg_query_rows == 384 - want
         plan.destroy()
 
 

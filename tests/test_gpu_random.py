@@ -44,9 +44,9 @@ def _case(seed):
 def test_random_micro_batch(oracle, seed):
     S, N, R, Z, Hq, Hkv, d, bm, bn, hs, fr = _case(seed)
     print(f"seed {seed}: S={S} N={N} R={R} cut={Z} heads={Hq}/{Hkv} d={d} bm={bm} bn={bn} head_split={hs} "
-          f"forward_rows={fr}", flush=True)
+          f"wg_query_rows={fr}", flush=True)
     w = W.Workload(f"rand{seed}", S, N, R, Hq, Hkv, d, d ** -0.5, 20_000 + seed, shard_cut=Z)
-    out = run_library(w, bm, bn, head_split=hs, forward_rows=fr)
+    out = run_library(w, bm, bn, head_split=hs, wg_query_rows=fr)
     f = widen(out["vals"])
     desc = oracle.ranges(S, N, R, Z)
     O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
