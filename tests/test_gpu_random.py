@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2505_19609_amd import workloads as W
-from gpu_util import run_library, widen
+from gpu_util import run_library, widen, bf16_ulp
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +55,10 @@ def test_random_micro_batch(oracle, seed):
                                 ("dQ", out["dq"], dQ, TOL_G), ("dK", out["dk"], dK, TOL_G),
                                 ("dV", out["dv"], dV, TOL_G)):
         assert np.isfinite(got).all(), name
-        err = float(np.abs(got - ref).max()) if got.size else 0.0
-        assert err <= tol, (name, err)
+        # max-abs tolerance; where the exact value is so large (|x| >= 16, e.g. dV of a one-token
+        # sequence summed over 7 query heads) that half the spacing of the bf16 output exceeds
+        # it, the correctly rounded output is the bound
+        allowed = np.maximum(tol, 0.502 * bf16_ulp(ref))
+        excess = float((np.abs(got - ref) - allowed).max()) if got.size else -1.0
+        assert excess <= 0.0, (name, excess)
     out["plan"].destroy()
