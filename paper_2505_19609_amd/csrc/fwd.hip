@@ -4,10 +4,12 @@
 // paper's cost model (App. B.2), the thing its scheduler balances.
 //
 // One workgroup = one work item (a block of BM query rows of one sequence) x
-// one query head.  It has 8 wavefronts (two per SIMD), each owning 32 query
-// rows, so it covers 256 rows.  The key / value prefix is streamed in tiles of
-// 64 rows through two rings of four LDS slots: two tiles are read while the next
-// two are fetched, and the workgroup meets at a barrier every second tile.
+// one query head, or a 128-row part of it.  In its large shape it has 8 wavefronts
+// (two per SIMD), each owning 32 query rows, so it covers 256 rows; the key / value
+// prefix is streamed in tiles of 64 rows through two rings of four LDS slots: two
+// tiles are read while the next two are fetched, and the workgroup meets at a
+// barrier every second tile.  The small shape (4 wavefronts, two-slot rings, two
+// workgroups per compute unit) is described at NW_SMALL below.
 //
 // Orientation (see mfma.h): every tile is computed TRANSPOSED so that the
 // query index is the MFMA column and therefore lane-local:
@@ -49,13 +51,13 @@ struct FwdParams {
 
 // Two shapes of the one kernel.  Large: 8 wavefronts = 256 query rows per workgroup and
 // 4 ring slots per operand (two tiles being read, two being fetched; a barrier every
-// second tile); its 139 KB of LDS leave room for one workgroup per compute unit.  Small
-// (items of at most 128 rows): 4 wavefronts and 2 ring slots (fetch one tile ahead, a
-// barrier every tile), 70 KB, so that two workgroups share a compute unit and the start-up
-// and drain of one (most of the run time of a short sequence) hide behind the other.
+// second tile); its 139 KB of LDS leave room for one workgroup per compute unit.  Small:
+// 4 wavefronts = 128 rows (a larger item is split over two workgroups) and 2 ring slots
+// (fetch one tile ahead, a barrier every tile), 70 KB, so that two workgroups share a
+// compute unit and the start-up, drain and barrier waits of one (most of the run time of
+// a short sequence) hide behind the other.  The plan chooses per micro-batch.
 constexpr int NW_LARGE = 8, NSLOT_LARGE = 4;
 constexpr int NW_SMALL = 4, NSLOT_SMALL = 2;
-
 
 // max / sum of a value over the two halves of the wavefront (lanes l and l ^ 32)
 // without going through LDS: two copies of x, the upper half of the first
