@@ -119,6 +119,7 @@ def main():
     pairs = int(plan.attended_pairs)
     useful = int(plan.useful_flops_fwd + plan.useful_flops_bwd)
     n_fwd_items, n_dkv_items = plan.n_fwd_items, plan.n_dkv_items
+    shape = {"wg_query_rows": int(plan.info.wg_query_rows), "head_split": int(plan.info.head_split)}
     plan.destroy()
 
     def step():
@@ -181,7 +182,7 @@ def main():
         "config": {"workload": w.name, "num_seqs": len(w.seq_len), "total_q": Tq, "total_k": Tk,
                    "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "attended_pairs": pairs,
                    "useful_flops_per_step": useful, "block_m": args.block_m or 256,
-                   "block_n": args.block_n or 128, "fwd_items": n_fwd_items, "dkv_items": n_dkv_items,
+                   "block_n": args.block_n or 128, "fwd_items": n_fwd_items, "dkv_items": n_dkv_items, **shape,
                    "step": "plan + fwd + bwd", "ms_plan": round(t_plan / args.steps * 1e3, 4)},
         "roofline": roofline,
     }

@@ -168,7 +168,8 @@ int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst
  * fp32 accumulation and softmax, O rounded to bf16 (nearest even), LSE fp32.
  * q, k, v (read) and o, lse (written) are DEVICE pointers in the layout above.
  * Only enqueues on `hip_stream`; never synchronises.
- * SKRULL_EINVAL on a null or misaligned pointer.
+ * SKRULL_EINVAL on a null or misaligned pointer, or when the current device is
+ * not the one the plan was made on.
  */
 int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
                     void *o, float *lse, void *hip_stream);
@@ -190,7 +191,8 @@ int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k
  * `workspace` is DEVICE scratch of at least info.bwd_workspace_bytes, 16-byte
  * aligned; contents on entry are ignored and on exit unspecified.
  * Only enqueues on `hip_stream`; never synchronises.
- * SKRULL_EINVAL on a null or misaligned pointer or a workspace that is too small.
+ * SKRULL_EINVAL on a null or misaligned pointer, a workspace that is too small,
+ * or when the current device is not the one the plan was made on.
  */
 int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
                     const void *o, const float *lse, const void *d_o,

@@ -56,6 +56,17 @@ int check_device(int *dev_out, int *compute_units)
     return SKRULL_OK;
 }
 
+// A plan's arrays live on the device it was made on: the calls that use them must run there.
+int check_plan_device(const skrull_attn_plan_t *plan)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) {
+        snprintf(g_err, sizeof g_err, "plan was made on device %d, current device is %d", plan->device, dev);
+        return SKRULL_EINVAL;
+    }
+    return SKRULL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -258,6 +269,7 @@ int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst
     default: return SKRULL_EINVAL;
     }
     if (bytes != n * sizeof(int32_t)) return SKRULL_EINVAL;
+    if (int rc = check_plan_device(plan)) return rc;
     hipError_t e = hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(export)");
     return SKRULL_OK;
@@ -269,6 +281,7 @@ int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k
     if (!plan) return SKRULL_EINVAL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
         return SKRULL_EINVAL;
+    if (int rc = check_plan_device(plan)) return rc;
     if (g_profile) (void)hipEventRecord(g_ev[0], (hipStream_t)hip_stream);
     hipError_t e = launch_fwd(plan, q, k, v, o, lse, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "forward launch");
@@ -288,6 +301,7 @@ int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k
     skrull_attn_plan_info_t info;
     skrull_attn_plan_info(plan, &info);
     if ((int64_t)workspace_bytes < info.bwd_workspace_bytes) return SKRULL_EINVAL;
+    if (int rc = check_plan_device(plan)) return rc;
     hipError_t e = launch_bwd(plan, q, k, v, o, lse, d_o, dq, dk, dv, (float *)workspace,
                               (hipStream_t)hip_stream, g_profile ? g_ev + 2 : nullptr);
     if (e != hipSuccess) return hip_fail(e, "backward launch");
