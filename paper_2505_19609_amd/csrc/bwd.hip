@@ -879,12 +879,15 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream
     if (ev) (void)hipEventRecord(ev[0], st);
     const int gq = p->n_fwd * p->Hq;
     const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + SUB - 1) / SUB);
-    if (D == 64 && p->wg_query_rows == 32 * NWQ_SMALL) {
-        const int subs = (p->BM + 32 * NWQ_SMALL - 1) / (32 * NWQ_SMALL);
-        dq_kernel<D, NWQ_SMALL><<<gq * subs, 64 * NWQ_SMALL, 0, st>>>(prm);
-    } else {
-        dq_kernel<D, NWQ_LARGE><<<gq, 64 * NWQ_LARGE, 0, st>>>(prm);
+    bool small_dq = false;
+    if constexpr (D == 64) {  // the small shape fits the LDS twice only at head_dim 64
+        if (p->wg_query_rows == 32 * NWQ_SMALL) {
+            const int subs = (p->BM + 32 * NWQ_SMALL - 1) / (32 * NWQ_SMALL);
+            dq_kernel<D, NWQ_SMALL><<<gq * subs, 64 * NWQ_SMALL, 0, st>>>(prm);
+            small_dq = true;
+        }
     }
+    if (!small_dq) dq_kernel<D, NWQ_LARGE><<<gq, 64 * NWQ_LARGE, 0, st>>>(prm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);

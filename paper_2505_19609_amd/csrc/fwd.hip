@@ -165,7 +165,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const int wrow0 = 32 * wave;
     const bool wave_active = wrow0 < rows;
     const int my_i = wrow0 + n;
-    const int my_pos = p0 + my_i;
     const int w_pmin = p0 + wrow0;
     const int w_pmax = p0 + min(wrow0 + 31, rows - 1);
     // half tiles (32 keys) of this wave: 0..L hold a visible key, those below n_full only visible keys
@@ -291,7 +290,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                 // per-register thresholds are formed here rather than kept for the whole kernel
                 int li = lane;
                 asm volatile("" : "+v"(li));
-                const int rel = p0 + wrow0 + (li & 31) - 32 * j - 4 * (li >> 5);  // my_pos - 32j - 4h
+                const int rel = p0 + wrow0 + (li & 31) - 32 * j - 4 * (li >> 5);  // this lane's query position - 32j - 4h
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[v] = (8 * (v >> 2) + (v & 3) > rel) ? -INFINITY : s[v];
             }
