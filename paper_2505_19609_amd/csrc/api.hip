@@ -202,8 +202,14 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
                          : (p->head_dim == 64 || longest_seq <= 8192) ? 128 : 256;
     plan->head_split = p->head_split;
     if (plan->head_split == 0) {
+        // Split only when the longest chain of the work list (its costliest item, all the
+        // heads of a group) exceeds an even share of the whole list over the compute units:
+        // then that chain bounds the kernel's time and shortening it pays for the fp32
+        // partial sums and their reduction; below that the unsplit kernel is 5-40 % faster
+        // (measured on 45 micro-batches of three head shapes; the ratio below was the
+        // dividing line at 1.0: splits won from 1.27 up, lost or tied up to 0.98).
         const double share = (double)totals.dkv_cost_sum * plan->Hkv / (double)compute_units;
-        const double want = share > 0.0 ? 2.0 * (double)totals.dkv_cost_max / share : 1.0;
+        const double want = share > 0.0 ? (double)totals.dkv_cost_max / share : 1.0;
         int32_t hs = want <= 1.0 ? 1 : (want >= (double)group ? group : (int32_t)ceil(want));
         // only equal shares: workgroups with different numbers of heads walk the query
         // tiles at different paces, stop sharing them in L2 and run 10 % slower (measured
