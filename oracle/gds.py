@@ -11,6 +11,9 @@ Readings (the listing is garbled or silent there):
   * Binpack is not named.  Reading: longest-processing-time greedy -- sequences by
     descending FLOPs (stable: equal costs keep the caller's order), each to the bin
     with the least load so far (lowest rank among equals).
+    The paper fixes no values for it (parity unpinned as far as the choice of algorithm
+    goes); the tests pin what any such greedy must satisfy: Graham's bound
+    (4/3 - 1/(3 ws)) against the brute-force optimum, and its special cases.
   * "init <- ceil(Sum(Subset)/C x N) - 1" is ceil(Sum / (C*N)) - 1: the loop adds one
     before its first use, so the first attempt is the smallest number of micro-batches
     the token constraint allows (at least 1).
