@@ -86,6 +86,47 @@ def test_edge_cases(oracle, name, heads, d):
     _exhaustive(oracle, w)
 
 
+@pytest.mark.parametrize("heads", [(5, 5), (16, 1), (24, 8), (40, 8), (9, 9), (10, 5)])
+def test_head_configurations(oracle, heads):
+    """Head counts that are not powers of two or do not divide the 8 dies the blocks are
+    dealt to (the block-to-head mapping must stay a bijection whatever Hkv is)."""
+    d = 64 if heads[0] % 2 else 128
+    w = W.Workload(f"heads{heads[0]}_{heads[1]}", [300, 65, 1, 190], [1, 1, 1, 2], [0, 0, 0, 1],
+                   heads[0], heads[1], d, d ** -0.5, 900 + heads[0])
+    _exhaustive(oracle, w)
+
+
+def test_thousands_of_tiny_sequences(oracle):
+    """3,000 sequences of 1 to 16 tokens: every work item is a sliver of one tile."""
+    rng = np.random.Generator(np.random.PCG64(3000))
+    S = [int(x) for x in rng.integers(1, 17, 3000)]
+    w = W.Workload("tiny3000", S, [1] * len(S), [0] * len(S), 4, 2, 64, 0.125, 3001)
+    _exhaustive(oracle, w)
+
+
+@pytest.mark.parametrize("scale,d", [(1.0, 64), (0.75, 128), (0.002, 128)])
+def test_extreme_logits(oracle, scale, d):
+    """Scores far outside the usual range: with softmax_scale 1 (0.75) on N(0,1) data of
+    head_dim 64 (128) they have a standard deviation of 8 and single rows reach +-40,
+    so probabilities span e^80 and the running maximum has to move; with 0.002 the
+    softmax is almost uniform.  (The forward lets the running maximum lag by up to 2^8.)"""
+    w = W.Workload(f"logits{scale}", [700, 1300, 64], [1, 1, 1], [0, 0, 0], 4, 2, d, scale, 4242)
+    out = run_library(w)
+    f = widen(out["vals"])
+    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
+    O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
+    dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
+    _report("O", out["o"], O, TOL_O)
+    _report("LSE", out["lse"], LSE, TOL_O)
+    # gradients grow with the scale (dQ, dK carry a factor softmax_scale): hold them to the
+    # stated bound relative to that factor where it exceeds 1/sqrt(d)
+    k = max(1.0, scale * d ** 0.5)
+    _report("dQ", out["dq"] / k, dQ / k, TOL_G)
+    _report("dK", out["dk"] / k, dK / k, TOL_G)
+    _report("dV", out["dv"], dV, TOL_G)
+    out["plan"].destroy()
+
+
 @pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (256, 256), (128, 64)])
 @pytest.mark.parametrize("d", [64, 128])
 def test_block_sizes(oracle, bm, bn, d):
