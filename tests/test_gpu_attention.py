@@ -161,6 +161,57 @@ def test_determinism_and_plan_reuse(oracle):
     plan.destroy()
 
 
+@pytest.mark.parametrize("d,cut", [(64, 0), (128, 1)])
+def test_nan_in_one_sequence_stays_there(oracle, d, cut):
+    """No cross-sequence leakage, the strict way: every value of one sequence is NaN, and the
+    results of all the others are bit-identical to a run on clean data (a probability of
+    zero times a NaN would still be a NaN, so no tile may even contain a neighbour's rows)."""
+    S, N, R = [200, 333, 70, 129, 1, 600], [1, 1, 1, 1, 1, 3], [0, 0, 0, 0, 0, 1]
+    Z = [0, 0, 0, 0, 0, cut]
+    w = W.Workload("poison", S, N, R, 6, 2, d, d ** -0.5, 1234, shard_cut=Z)
+    clean = run_library(w)
+    desc = oracle.ranges(S, N, R, Z)
+    nan_bits = np.uint16(0x7FC0)
+    for victim in (2, 5, 0):
+        vals = {n: a.copy() for n, a in clean["vals"].items()}
+        # rows of the poisoned sequence in the packed tensors
+        q_lo, q_hi = _rows_of(desc, victim, "cu_q")
+        k_lo, k_hi = _rows_of(desc, victim, "cu_k")
+        for n in ("q", "do"):
+            vals[n][q_lo:q_hi] = nan_bits
+        for n in ("k", "v"):
+            vals[n][k_lo:k_hi] = nan_bits
+        out = run_library(w, vals=vals)
+        for n, (lo, hi) in (("o", (q_lo, q_hi)), ("dq", (q_lo, q_hi)), ("dk", (k_lo, k_hi)), ("dv", (k_lo, k_hi))):
+            keep = np.ones(out[n].shape[0], bool)
+            keep[lo:hi] = False
+            assert np.array_equal(out[n][keep], clean[n][keep]), (victim, n)
+        keep = np.ones(out["lse"].shape[1], bool)
+        keep[q_lo:q_hi] = False
+        assert np.array_equal(out["lse"][:, keep], clean["lse"][:, keep]), (victim, "lse")
+        out["plan"].destroy()
+    clean["plan"].destroy()
+
+
+def _rows_of(desc, k, cu):
+    """Packed row range [lo, hi) of sequence k (its one or two query segments / its prefix)."""
+    segs = [i for i, q in enumerate(_segment_owner(desc)) if q == k]
+    if cu == "cu_q":
+        return int(desc["cu_q"][segs[0]]), int(desc["cu_q"][segs[-1] + 1])
+    return int(desc["cu_k"][segs[0]]), int(desc["cu_k"][segs[-1] + 1])
+
+
+def _segment_owner(desc):
+    """Sequence index of every query segment: a segment that shares the prefix of the one
+    before it belongs to the same sequence."""
+    owner, k = [], -1
+    for sh in desc["shares_kv"]:
+        if not sh:
+            k += 1
+        owner.append(k)
+    return owner
+
+
 def test_sequence_order_permutes_outputs(oracle):
     """The library is agnostic to the order of sequences in the packed batch."""
     S, N, R = [300, 64, 1000, 129], [1, 1, 4, 1], [0, 0, 2, 0]
