@@ -493,6 +493,17 @@ def test_head_split_is_chosen_from_the_work_list():
         with pytest.raises(B.SkrullError):
             B.skrull_attn_plan(w2.seq_len, w2.shard_degree, w2.shard_index, 14, 2, 64, 0.125, head_split=bad)
     p2.destroy(); p3.destroy()
+    # the split follows r = longest chain / even share of the list over 256 compute units:
+    # none up to r = 1, then the smallest divisor of the group size that is at least r
+    for S, (hq, hkv, d), want in (([1024] * 16, (28, 4, 128), 1),   # r = 0.80
+                                  ([4096] * 4, (28, 4, 128), 1),    # r = 0.94
+                                  ([2048], (14, 2, 64), 7),         # r = 14
+                                  ([4096], (32, 8, 128), 2),        # r = 1.88
+                                  ([2048], (32, 8, 128), 4),        # r = 3.56
+                                  ([8192] * 4, (14, 2, 64), 1)):    # r = 0.97
+        p = B.skrull_attn_plan(S, [1] * len(S), [0] * len(S), hq, hkv, d, d ** -0.5)
+        assert p.head_split == want, (S, hq, hkv, p.head_split)
+        p.destroy()
 
 
 @pytest.mark.parametrize("rows", [128, 256])
