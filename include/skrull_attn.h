@@ -60,7 +60,7 @@ typedef struct {
     int32_t        head_dim;      /* 64 or 128                                                 */
     float          softmax_scale; /* finite, > 0; multiplies Q.K^T inside the kernels          */
     int32_t        block_m;       /* query rows per work item: 64, 128 or 256; 0 = 256          */
-    int32_t        block_n;       /* key rows per dK/dV work item: 64, 128 or 256; 0 = 128      */
+    int32_t        block_n;       /* key rows per dK/dV work item: 64, 128, 192 or 256; 0 = library's choice */
     const int32_t *shard_cut;     /* [K] HOST or NULL (= all SKRULL_CUT_CONTIGUOUS)             */
     int32_t        head_split;    /* dK/dV workgroups per KV group, 1..Hq/Hkv; 0 = library's choice */
     int32_t        wg_query_rows; /* query rows per forward / dQ workgroup: 128 or 256; 0 = library's choice */
@@ -140,7 +140,7 @@ enum {
  * [0, degree), more chunks than tokens (degree > S_k, or 2*degree > S_k for a
  * two-chunk cut), a cut other than the two above, head_split outside [0, Hq/Hkv],
  * wg_query_rows other than 0/128/256, Hq % Hkv != 0, head_dim not 64/128, a block size
- * other than 0/64/128/256, scale not finite/positive, a total of 2^31 rows or
+ * other than 0/64/128/256 (block_n also 192), scale not finite/positive, a total of 2^31 rows or
  * more, more than 2^20 work items in either list, or a sequence too long for
  * the kernels' 32-bit tile offsets: (rows of this rank's longest chunk + 256)
  * * Hq * d * 2 bytes and (S_k + 256) * Hkv * d * 2 bytes must both stay below

@@ -49,8 +49,6 @@ struct BwdParams {
 // ---------------------------------------------------------------------------
 // dQ
 // ---------------------------------------------------------------------------
-constexpr int NW = 4;          // (dK/dV) pairs of waves per workgroup
-constexpr int SUB = 32 * NW;   // key rows per dK/dV pass
 // The dQ kernel comes in two shapes, like the forward: 8 wavefronts (256 query rows) with a
 // five-slot K ring and a four-slot V ring, one workgroup per compute unit; and, where two of
 // them fit the LDS together (head_dim 64), 4 wavefronts (128 rows) with three K slots and two
@@ -452,23 +450,29 @@ __device__ __forceinline__ void ds_quad(uint32_t p01, uint32_t p23, const float 
                  : "v"(p01), "v"(p23), "v"(g[0]), "v"(g[1]), "v"(g[2]), "v"(g[3]));
 }
 
-constexpr int NWP = 8;  // 4 S waves + 4 dP waves
+// PAIRS wave pairs per workgroup: 4 (8 wavefronts, 128 key rows, two wavefronts per SIMD), or,
+// at head_dim 64 where 136 registers and 106 KB of LDS allow it, 6 (12 wavefronts, 192 key
+// rows, three per SIMD): more wavefronts to overlap with and a third fewer fetches of each
+// query tile.  The 12-wavefront shape serves work items of block_n = 192.
+constexpr int PAIRS_8W = 4, PAIRS_12W = 6;
 
-template <int D>
-__global__ __launch_bounds__(64 * NWP, 2) void dkv_kernel(const BwdParams prm)
+template <int D, int PAIRS>
+__global__ __launch_bounds__(128 * PAIRS, PAIRS == PAIRS_12W ? 3 : 2) void dkv_kernel(const BwdParams prm)
 {
+    constexpr int NWP = 2 * PAIRS;   // wavefronts: PAIRS S waves, then PAIRS dP waves
+    constexpr int SUB = 32 * PAIRS;  // key rows per workgroup
     constexpr int KS = D / 16, TT = D / 32, QT = TILE_ROWS;
     constexpr int TB = TileGeom<D>::BYTES;
     constexpr int SLOT = 2 * TB + 2 * QT * 4;  // Q rows | dO rows | LSE*log2e | D
     __shared__ __align__(16) unsigned char lds_ring[3][SLOT];
-    __shared__ __align__(16) unsigned char lds_p[4][2][4][1024];  // [pair][round parity][16-row block][lane*16]
+    __shared__ __align__(16) unsigned char lds_p[PAIRS][2][4][1024];  // [pair][round parity][16-row block][lane*16]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int role = wave >> 2, pw = wave & 3;  // waves w and w+4 share 32 key rows
+    const int role = wave / PAIRS, pw = wave % PAIRS;  // waves w and w+PAIRS share 32 key rows
     const int n = lane & 31, h = lane >> 5;
-    // blockIdx -> (item, 128-key pass of the item, KV head); an item of block_n = 256
-    // key rows is two workgroups
+    // blockIdx -> (item, SUB-key pass of the item, KV head); an item of more key rows
+    // than SUB is several workgroups
     const int passes = (prm.BN + SUB - 1) / SUB;
     const int sub = blockIdx.x % passes;
     const int hs = prm.head_split;
@@ -878,7 +882,6 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream
     // which dK/dV reads.  Events: ev[0] start, ev[1] after dQ, ev[2] after dK/dV.
     if (ev) (void)hipEventRecord(ev[0], st);
     const int gq = p->n_fwd * p->Hq;
-    const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + SUB - 1) / SUB);
     bool small_dq = false;
     if constexpr (D == 64) {  // the small shape fits the LDS twice only at head_dim 64
         if (p->wg_query_rows == 32 * NWQ_SMALL) {
@@ -891,7 +894,18 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    dkv_kernel<D><<<gk, 64 * NWP, 0, st>>>(prm);
+    {
+        const int pairs = (D == 64 && p->BN == 32 * PAIRS_12W) ? PAIRS_12W : PAIRS_8W;
+        const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + 32 * pairs - 1) / (32 * pairs));
+        bool done = false;
+        if constexpr (D == 64) {
+            if (pairs == PAIRS_12W) {
+                dkv_kernel<D, PAIRS_12W><<<gk, 128 * PAIRS_12W, 0, st>>>(prm);
+                done = true;
+            }
+        }
+        if (!done) dkv_kernel<D, PAIRS_8W><<<gk, 128 * PAIRS_8W, 0, st>>>(prm);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p->head_split > 1) {

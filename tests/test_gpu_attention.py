@@ -127,7 +127,7 @@ def test_extreme_logits(oracle, scale, d):
     out["plan"].destroy()
 
 
-@pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (256, 256), (128, 64)])
+@pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (256, 256), (128, 64), (0, 192), (64, 192)])
 @pytest.mark.parametrize("d", [64, 128])
 def test_block_sizes(oracle, bm, bn, d):
     w = W.Workload("blocks", [700, 129, 1030, 64], [1, 1, 2, 1], [0, 0, 1, 0], 4, 2, d, d ** -0.5, 77)
@@ -419,7 +419,7 @@ def test_two_chunk_cut(oracle, name, heads, d):
     _exhaustive(oracle, w)
 
 
-@pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (128, 128)])
+@pytest.mark.parametrize("bm,bn", [(64, 64), (64, 256), (256, 64), (128, 128), (0, 192)])
 def test_two_chunk_cut_block_sizes(oracle, bm, bn):
     w = W.Workload("blocks2", [2100, 129, 1500], [3, 1, 2], [1, 0, 0], 4, 2, 128, 128 ** -0.5, 78,
                    shard_cut=[1, 0, 1])
@@ -501,7 +501,7 @@ def test_head_split_is_chosen_from_the_work_list():
                                   ([4096], (32, 8, 128), 2),        # r = 1.88
                                   ([2048], (32, 8, 128), 4),        # r = 3.56
                                   ([8192] * 4, (14, 2, 64), 1)):    # r = 0.97
-        p = B.skrull_attn_plan(S, [1] * len(S), [0] * len(S), hq, hkv, d, d ** -0.5)
+        p = B.skrull_attn_plan(S, [1] * len(S), [0] * len(S), hq, hkv, d, d ** -0.5, block_n=128)   # r is for 128-key items
         assert p.head_split == want, (S, hq, hkv, p.head_split)
         p.destroy()
 
@@ -529,6 +529,21 @@ def test_workgroup_shape_is_chosen_from_head_dim_and_length():
         plan = B.skrull_attn_plan(S, n, [0] * len(S), 8, 2, d, d ** -0.5, wg_query_rows=384 - want)
         assert plan.info.wg_query_rows == 384 - want
         plan.destroy()
+
+
+def test_dkv_block_is_chosen_from_head_dim_and_shape_of_the_work():
+    """block_n left open: 192 (the 12-wavefront dK/dV shape) at head_dim 64 when the work is
+    mostly in the triangles of sequences of at least 8,192 tokens, else 128."""
+    from paper_2505_19609_amd import binding as B
+    for S, N, R, d, want in (([16384], [1], [0], 64, 192), ([8192] * 4, [1] * 4, [0] * 4, 64, 192),
+                             ([1024] * 32, [1] * 32, [0] * 32, 64, 128), ([65536], [8], [7], 64, 128),
+                             ([65536], [8], [0], 64, 192), ([16384], [1], [0], 128, 128)):
+        plan = B.skrull_attn_plan(S, N, R, 14, 2, d, d ** -0.5)
+        assert plan.block_n == want, (S, N, R, d, plan.block_n)
+        plan.destroy()
+    plan = B.skrull_attn_plan([16384], [1], [0], 14, 2, 64, 0.125, block_n=128)
+    assert plan.block_n == 128
+    plan.destroy()
 
 
 def test_autograd_wrapper(oracle):

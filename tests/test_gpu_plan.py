@@ -20,7 +20,7 @@ def _check(oracle, S, N, R, Hq, Hkv, d, bm, bn, cut=None):
     desc = oracle.ranges(S, N, R, cut)
     assert plan.num_seqs == len(S) and plan.num_segments == desc["num_seqs"]
     BM, BN = plan.block_m, plan.block_n
-    assert (BM, BN) == (bm or 256, bn or 128)
+    assert BM == (bm or 256) and (BN == bn if bn else BN in (128, 192))   # 0: the library's choice
     assert plan.total_q == desc["total_q"] and plan.total_k == desc["total_k"]
     assert plan.attended_pairs == oracle.attended_pairs(desc)
     assert plan.useful_flops_fwd == 4 * plan.attended_pairs * d * Hq
@@ -36,7 +36,7 @@ def _check(oracle, S, N, R, Hq, Hkv, d, bm, bn, cut=None):
 
 
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5])
-@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 256), (256, 64)])
+@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 256), (256, 64), (128, 192)])
 def test_plan_matches_oracle_on_benchmark_configs(oracle, n, bm, bn):
     w = W.config(n)
     _check(oracle, w.seq_len, w.shard_degree, w.shard_index, w.num_q_heads, w.num_kv_heads, w.head_dim, bm, bn)
@@ -46,7 +46,7 @@ def test_plan_matches_oracle_on_benchmark_configs(oracle, n, bm, bn):
 
 
 @pytest.mark.parametrize("name", sorted(CASES))
-@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 64), (128, 256)])
+@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 64), (128, 256), (256, 192)])
 def test_plan_matches_oracle_on_edge_cases(oracle, name, bm, bn):
     S, N, R = CASES[name]
     _check(oracle, S, N, R, 4, 2, 64, bm, bn)
@@ -61,7 +61,7 @@ TWO_CHUNK_CASES = {
 
 
 @pytest.mark.parametrize("name", sorted(TWO_CHUNK_CASES))
-@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 64), (128, 256), (256, 64)])
+@pytest.mark.parametrize("bm,bn", [(0, 0), (64, 64), (128, 256), (256, 64), (64, 192)])
 def test_plan_matches_oracle_with_two_chunk_cuts(oracle, name, bm, bn):
     S, N, R, Z = TWO_CHUNK_CASES[name]
     _check(oracle, S, N, R, 4, 2, 64, bm, bn, cut=Z)

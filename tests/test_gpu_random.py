@@ -37,6 +37,8 @@ def _case(seed):
     bn = int(rng.choice([0, 64, 128, 256]))
     hs = int(rng.integers(0, g + 1))
     fr = int(rng.choice([0, 128, 256]))   # drawn last: the other parameters of a seed stay what they were
+    if rng.integers(0, 4) == 0:
+        bn = 192                           # (drawn after everything else, for the same reason)
     return S, N, R, Z, Hkv * g, Hkv, d, bm, bn, hs, fr
 
 
