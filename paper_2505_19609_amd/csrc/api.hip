@@ -231,8 +231,13 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         // partial sums and their reduction; below that the unsplit kernel is 5-40 % faster
         // (measured on 45 micro-batches of three head shapes; the ratio below was the
         // dividing line at 1.0: splits won from 1.27 up, lost or tied up to 0.98).
+        // The 12-wavefront shape (fewer, larger workgroups: rounding of workgroups per compute
+        // unit weighs more) gains from the split from half that ratio on: at 14/2 heads x 64
+        // every batch measured from 2 x 8,192 to 65,536 tokens was 7-50 % faster split 7 ways
+        // (65,536 tokens, ratio 0.75: 17.4 -> 16.1 ms; eight 8,192-token sequences, 0.72: equal).
         const double share = (double)totals.dkv_cost_sum * plan->Hkv / (double)compute_units;
-        const double want = share > 0.0 ? (double)totals.dkv_cost_max / share : 1.0;
+        const double scale = (plan->d == 64 && plan->BN == 192) ? 2.0 : 1.0;
+        const double want = share > 0.0 ? scale * (double)totals.dkv_cost_max / share : 1.0;
         int32_t hs = want <= 1.0 ? 1 : (want >= (double)group ? group : (int32_t)ceil(want));
         // only equal shares: workgroups with different numbers of heads walk the query
         // tiles at different paces, stop sharing them in L2 and run 10 % slower (measured
