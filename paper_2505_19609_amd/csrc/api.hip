@@ -97,10 +97,6 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     const int64_t q_row_bytes = (int64_t)p->num_q_heads * p->head_dim * 2;
     const int64_t kv_row_bytes = (int64_t)p->num_kv_heads * p->head_dim * 2;
     int64_t cap_fwd = 0, cap_dkv = 0, cap_dkv_192 = 0;
-    // attended pairs below the diagonal blocks' triangle (keys before the segment's first
-    // query: every key block there meets ALL query tiles, so the dK/dV chains are equally
-    // long) and inside it (chains of every length)
-    double pairs_prefix = 0.0, pairs_triangle = 0.0;
     for (int32_t k = 0; k < K; ++k) {
         const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
         const int32_t z = p->shard_cut ? p->shard_cut[k] : SKRULL_CUT_CONTIGUOUS;
@@ -120,22 +116,14 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         cap_fwd += (1 + z) * ((longest + BM - 1) / BM);
         cap_dkv += ((int64_t)s + BN - 1) / BN;
         cap_dkv_192 += ((int64_t)s + 191) / 192;
-        for (int32_t part = 0; part <= z; ++part) {
-            const int64_t c = part == 0 ? r : 2 * (int64_t)n - 1 - r;
-            const int64_t qb = c * s / chunks, qe = (c + 1) * s / chunks;
-            pairs_prefix += (double)(qe - qb) * (double)qb;
-            pairs_triangle += 0.5 * (double)(qe - qb) * (double)(qe - qb + 1);
-        }
     }
     // dK/dV block size when the caller leaves it open.  At head_dim 64 the kernel has a
-    // 12-wavefront shape over 192 key rows; on micro-batches whose work is mostly in the
-    // triangles of sequences of 8,192 tokens or more it was 3-16 % faster than the
-    // 8-wavefront shape over 128 (14 query / 2 KV heads; 4 x 8,192 ... 65,536 tokens and
-    // the benchmark length mixes).  Where most of the work lies before the queries (slices
-    // of distributed sequences: equally long chains, few of them per compute unit) or the
-    // sequences are short, fewer and larger workgroups lose to the rounding of workgroups
-    // per compute unit (a 1/8 slice of 65,536 tokens: 14 % slower), so those keep 128.
-    if (p->block_n == 0 && p->head_dim == 64 && longest_seq >= 8192 && pairs_prefix <= pairs_triangle) {
+    // 12-wavefront shape over 192 key rows; with a sequence of 8,192 tokens or more in the
+    // micro-batch it was 3-16 % faster than the 8-wavefront shape over 128 on whole sequences
+    // and on slices of distributed ones alike (14 query / 2 KV heads; 2 x 8,192 ... 98,304
+    // tokens, both cuts, the benchmark length mixes); on short sequences the fewer, larger
+    // workgroups lose to the rounding of workgroups per compute unit, so those keep 128.
+    if (p->block_n == 0 && p->head_dim == 64 && longest_seq >= 8192) {
         BN = 192;
         cap_dkv = cap_dkv_192;
     }

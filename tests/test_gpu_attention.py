@@ -532,11 +532,11 @@ def test_workgroup_shape_is_chosen_from_head_dim_and_length():
 
 
 def test_dkv_block_is_chosen_from_head_dim_and_shape_of_the_work():
-    """block_n left open: 192 (the 12-wavefront dK/dV shape) at head_dim 64 when the work is
-    mostly in the triangles of sequences of at least 8,192 tokens, else 128."""
+    """block_n left open: 192 (the 12-wavefront dK/dV shape) at head_dim 64 when a sequence
+    of at least 8,192 tokens is present, else 128."""
     from paper_2505_19609_amd import binding as B
     for S, N, R, d, want in (([16384], [1], [0], 64, 192), ([8192] * 4, [1] * 4, [0] * 4, 64, 192),
-                             ([1024] * 32, [1] * 32, [0] * 32, 64, 128), ([65536], [8], [7], 64, 128),
+                             ([1024] * 32, [1] * 32, [0] * 32, 64, 128), ([65536], [8], [7], 64, 192), ([8191], [1], [0], 64, 128),
                              ([65536], [8], [0], 64, 192), ([16384], [1], [0], 128, 128)):
         plan = B.skrull_attn_plan(S, N, R, 14, 2, d, d ** -0.5)
         assert plan.block_n == want, (S, N, R, d, plan.block_n)
