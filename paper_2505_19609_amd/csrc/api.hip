@@ -97,6 +97,9 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     const int64_t q_row_bytes = (int64_t)p->num_q_heads * p->head_dim * 2;
     const int64_t kv_row_bytes = (int64_t)p->num_kv_heads * p->head_dim * 2;
     int64_t cap_fwd = 0, cap_dkv = 0, cap_dkv_192 = 0;
+    // cost (query blocks of BM rows) of the dK/dV items there would be with 128 key rows:
+    // their sum and maximum, for the choice of block_n below
+    int64_t cost128_sum = 0, cost128_max = 0;
     for (int32_t k = 0; k < K; ++k) {
         const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
         const int32_t z = p->shard_cut ? p->shard_cut[k] : SKRULL_CUT_CONTIGUOUS;
@@ -116,22 +119,51 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         cap_fwd += (1 + z) * ((longest + BM - 1) / BM);
         cap_dkv += ((int64_t)s + BN - 1) / BN;
         cap_dkv_192 += ((int64_t)s + 191) / 192;
-    }
-    // dK/dV block size when the caller leaves it open.  At head_dim 64 the kernel has a
-    // 12-wavefront shape over 192 key rows; with a sequence of 8,192 tokens or more in the
-    // micro-batch it was 3-16 % faster than the 8-wavefront shape over 128 on whole sequences
-    // and on slices of distributed ones alike (14 query / 2 KV heads; 2 x 8,192 ... 98,304
-    // tokens, both cuts, the benchmark length mixes); on short sequences the fewer, larger
-    // workgroups lose to the rounding of workgroups per compute unit, so those keep 128.
-    if (p->block_n == 0 && p->head_dim == 64 && longest_seq >= 8192) {
-        BN = 192;
-        cap_dkv = cap_dkv_192;
+        if (p->block_n == 0 && p->head_dim == 64 && s < 8192) {
+            // this rank's one or two chunks [qb, qe) of the sequence; a key block costs the
+            // query blocks of each chunk from the first row at or after the block's first key
+            const int64_t c_lo = r, c_hi = z ? 2 * (int64_t)n - 1 - r : r;
+            const int64_t kv_end = (c_hi + 1) * s / chunks;
+            for (int64_t j0 = 0; j0 < kv_end; j0 += 128) {
+                int64_t cost = 0;
+                for (int64_t c = c_lo;; c = c_hi) {
+                    const int64_t qb = c * s / chunks, qe = (c + 1) * s / chunks;
+                    if (j0 < qe) {
+                        const int64_t i0 = j0 > qb ? j0 - qb : 0;
+                        cost += (qe - qb + BM - 1) / BM - i0 / BM;
+                    }
+                    if (c == c_hi) break;
+                }
+                cost128_sum += cost;
+                cost128_max = cost > cost128_max ? cost : cost128_max;
+            }
+        }
     }
     if (n_seg > INT32_MAX / 2) return SKRULL_EINVAL;
     if (cap_fwd > 8 * (int64_t)kMaxItems || cap_dkv > 8 * (int64_t)kMaxItems) return SKRULL_EINVAL;
     int dev = 0, compute_units = 0;
     int rc = check_device(&dev, &compute_units);
     if (rc != SKRULL_OK) return rc;
+
+    // dK/dV block size when the caller leaves it open.  At head_dim 64 the kernel has a
+    // 12-wavefront shape over 192 key rows; with a sequence of 8,192 tokens or more in the
+    // micro-batch it was 3-16 % faster than the 8-wavefront shape over 128 on whole sequences
+    // and on slices of distributed ones alike (14 query / 2 KV heads; 2 x 8,192 ... 98,304
+    // tokens, both cuts, the benchmark length mixes).  On shorter sequences it wins (7-14 %)
+    // exactly where the work list is so short that the heads are split anyway (longest
+    // chain above an even share of 128-key items, see head_split below), and loses 2-25 %
+    // where it is not: there the fewer, larger workgroups and the split they then need
+    // cost more than the third wavefront per SIMD brings.
+    if (p->block_n == 0 && p->head_dim == 64) {
+        bool take192 = longest_seq >= 8192;
+        if (!take192 && cost128_sum > 0) {
+            take192 = (double)cost128_max > (double)cost128_sum * p->num_kv_heads / compute_units;
+        }
+        if (take192) {
+            BN = 192;
+            cap_dkv = cap_dkv_192;
+        }
+    }
 
     hipStream_t st = (hipStream_t)hip_stream;
     skrull_attn_plan_t *plan = nullptr;

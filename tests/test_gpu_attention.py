@@ -533,10 +533,12 @@ def test_workgroup_shape_is_chosen_from_head_dim_and_length():
 
 def test_dkv_block_is_chosen_from_head_dim_and_shape_of_the_work():
     """block_n left open: 192 (the 12-wavefront dK/dV shape) at head_dim 64 when a sequence
-    of at least 8,192 tokens is present, else 128."""
+    of at least 8,192 tokens is present or the work list is short enough for the head
+    split (longest chain above an even share of the 128-key items), else 128."""
     from paper_2505_19609_amd import binding as B
     for S, N, R, d, want in (([16384], [1], [0], 64, 192), ([8192] * 4, [1] * 4, [0] * 4, 64, 192),
-                             ([1024] * 32, [1] * 32, [0] * 32, 64, 128), ([65536], [8], [7], 64, 192), ([8191], [1], [0], 64, 128),
+                             ([1024] * 32, [1] * 32, [0] * 32, 64, 128), ([65536], [8], [7], 64, 192), ([8191], [1], [0], 64, 192), ([4096] * 8, [1] * 8, [0] * 8, 64, 128),
+                             ([4096] * 2, [1] * 2, [0] * 2, 64, 192), ([3000] + [700] * 30, [1] * 31, [0] * 31, 64, 192),
                              ([65536], [8], [0], 64, 192), ([16384], [1], [0], 128, 128)):
         plan = B.skrull_attn_plan(S, N, R, 14, 2, d, d ** -0.5)
         assert plan.block_n == want, (S, N, R, d, plan.block_n)
