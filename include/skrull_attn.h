@@ -128,7 +128,17 @@ enum {
  * reads the prefix; m0 = that segment's first query block that can see the
  * block, cost n_q = number of query blocks that do (of both segments when the
  * prefix is shared).  Ties keep (segment, block) ascending order, so the layout
- * is a pure function of the inputs.
+ * is a pure function of the inputs and of the block sizes in effect.
+ *
+ * Tuning fields left at 0 are chosen by the library from the head shape, the
+ * lengths and the device's compute-unit count, and skrull_attn_plan_info
+ * reports what is in effect: block_n is 128, or 192 at head_dim 64 when a
+ * sequence of 8,192 tokens or more is present or the work list is short (the
+ * dK/dV kernel then runs 12 wavefronts over 192 key rows); head_split above 1
+ * when the longest dK/dV chain exceeds an even share of the work list;
+ * wg_query_rows 128 at head_dim 64 and for micro-batches without sequences
+ * above 8,192 tokens, else 256.  None of them changes a result beyond the
+ * last bit of dK/dV (head_split changes the order of the sum over heads).
  *
  * p and the three arrays it points to are HOST memory, read before return.
  * `hip_stream` (a hipStream_t, may be NULL for the default stream) carries the
