@@ -518,6 +518,21 @@ def test_workgroup_shapes(oracle, rows, d, bm):
     _exhaustive(oracle, w, block_m=bm, wg_query_rows=rows)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_shapes_and_block_sizes_change_no_bit(d):
+    """The workgroup shape of forward / dQ and the dK/dV block size (8 or 12 wavefronts at
+    head_dim 64) only regroup the work: every result is bit-identical."""
+    w = W.Workload("bitid", [1, 63, 129, 700, 1411, 2600, 5000], [1] * 6 + [2], [0] * 6 + [1], 4, 2, d, d ** -0.5, 77)
+    base = run_library(w, wg_query_rows=128, head_split=1, block_n=128)
+    for kw in (dict(wg_query_rows=256, block_n=128), dict(wg_query_rows=128, block_n=192),
+               dict(wg_query_rows=256, block_n=256, block_m=64)):
+        other = run_library(w, head_split=1, **kw)
+        for n in ("o", "lse", "dq", "dk", "dv"):
+            assert np.array_equal(base[n], other[n]), (kw, n)
+        other["plan"].destroy()
+    base["plan"].destroy()
+
+
 def test_workgroup_shape_is_chosen_from_head_dim_and_length():
     from paper_2505_19609_amd import binding as B
     for S, d, want in (([8192, 100], 128, 128), ([8193, 100], 128, 256), ([65536], 64, 128),
