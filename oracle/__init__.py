@@ -215,6 +215,21 @@ def bwd_dq_rows(q, k, v, do, desc, scale, entries):
     return dQ, D
 
 
+def delta_rows(do_rows, o_rows):
+    """D [n] (float64) from rows of dO and of the forward's O: D_i = sum_t dO_i[t] * O_i[t],
+    the row term of the softmax gradient dS_ij = P_ij (dP_ij - D_i).  ``o_rows`` is the
+    float64 O that :func:`fwd_rows` returned for the same (seq, head, row) triples and
+    ``do_rows`` the matching rows of dO; bwd_dq_rows returns the same D (pinned against it
+    in tests/test_oracle_attention.py) but recomputes the whole row to get it."""
+    do_rows = np.asarray(do_rows, np.float64)
+    o_rows = np.asarray(o_rows, np.float64)
+    assert do_rows.shape == o_rows.shape and do_rows.ndim == 2
+    D = np.zeros(do_rows.shape[0], np.float64)
+    for t in range(do_rows.shape[1]):
+        D += do_rows[:, t] * o_rows[:, t]
+    return D
+
+
 def bwd_dkv_cols(q, k, v, do, lse_full, d_full, desc, scale, entries):
     """dK, dV [n, d] (float64) for the listed (seq, kv head, key position) triples.
 

@@ -2,7 +2,10 @@
 
 Tolerances are the stated ones: max-abs 2e-2 on O (and LSE), 5e-2 on dQ/dK/dV,
 GPU bf16 outputs widened and compared with the unrounded fp64 oracle on the
-same seeded bf16 inputs.  Small cases are compared exhaustively; the full-size
+same seeded bf16 inputs.  Two exceptions, both where gradients carry 8x the usual
+softmax scale: config 1 as stated adds one spacing of bf16 relative to the element
+(RTOL_8X: elements exceed 16 there and a bf16 output cannot meet 5e-2), and the
+out-of-distribution stress test_extreme_logits scales the bound by that factor.  Small cases are compared exhaustively; the full-size
 benchmark micro-batches on seeded samples of rows / columns that the oracle
 computes one by one, plus properties that hold at any size."""
 import numpy as np
@@ -16,21 +19,34 @@ pytestmark = pytest.mark.gpu
 TOL_O, TOL_G = 2e-2, 5e-2
 
 
-def _report(name, got, ref, tol):
+def _report(name, got, ref, tol, rtol=0.0):
+    """Max-abs check; with ``rtol`` an element's bound is tol + rtol * |reference value|."""
     err = np.abs(got.astype(np.float64) - ref)
     if err.size == 0:
         return 0.0
-    i = np.unravel_index(np.argmax(err), err.shape)
+    allowed = tol + rtol * np.abs(ref)
+    i = np.unravel_index(np.argmax(err - allowed), err.shape)
     ulps = err[i] / bf16_ulp(ref[i])
-    msg = (f"{name}: max-abs {err[i]:.4g} at {i} (ref {ref[i]:.6g}, got {got[i]:.6g}, "
-           f"{ulps:.2f} bf16 ulp), tol {tol}")
+    msg = (f"{name}: max-abs {err.max():.4g}; worst against its bound {err[i]:.4g} at {i} (ref {ref[i]:.6g}, "
+           f"got {got[i]:.6g}, {ulps:.2f} bf16 ulp), bound {allowed[i]:.4g}")
     print(msg)
     assert np.isfinite(got).all(), f"{name}: non-finite output"
-    assert err[i] <= tol, msg
+    assert err[i] <= allowed[i], msg
     return float(err[i])
 
 
-def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G, head_split=0, wg_query_rows=0):
+# Relative part of the bound for config 1 as stated, whose dQ carries 8x the usual softmax
+# scale: elements reach |x| > 16 and the stated max-abs
+# 5e-2 is below the spacing of the bf16 output (0.125): one spacing of bf16 relative to the
+# reference value, 2^-7.  Three bf16 roundings of relative size 2^-9 lie on the path of a
+# gradient element (the forward's O, from which D = dO.O is formed; dS before the second
+# product; the output itself), and in a query row that sees only a few keys nothing averages
+# them out.  Observed worst (config 1 as stated): 0.0745 on dQ = -15.637 and 0.054 on -7.836,
+# both in a row with three keys; 0.0888 on |dQ| > 16.  Elements of ordinary size keep 5e-2.
+RTOL_8X = 2.0 ** -7
+
+
+def _exhaustive(oracle, w, block_m=0, block_n=0, rtol=0.0, head_split=0, wg_query_rows=0, keep=False):
     out = run_library(w, block_m, block_n, head_split=head_split, wg_query_rows=wg_query_rows)
     if wg_query_rows:
         assert out["plan"].info.wg_query_rows == wg_query_rows
@@ -40,27 +56,36 @@ def _exhaustive(oracle, w, block_m=0, block_n=0, tol_dq=TOL_G, head_split=0, wg_
     dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
     _report("O", out["o"], O, TOL_O)
     _report("LSE", out["lse"], LSE, TOL_O)
-    _report("dQ", out["dq"], dQ, tol_dq)
-    _report("dK", out["dk"], dK, TOL_G)
-    _report("dV", out["dv"], dV, TOL_G)
-    out["plan"].destroy()
+    _report("dQ", out["dq"], dQ, TOL_G, rtol)
+    _report("dK", out["dk"], dK, TOL_G, rtol)
+    _report("dV", out["dv"], dV, TOL_G, rtol)
+    if not keep:
+        out["plan"].destroy()
+    return out
 
 
 def test_config1_tiny_literal(oracle):
-    """Config 1 as stated: Q pre-scaled by 1/8 in the data, no further scale.
-    dQ is then the gradient w.r.t. the pre-scaled Q, 8x the gradient w.r.t. the
-    N(0,1) draw; bf16 rounding of the exact result alone errs by 0.060 there
-    (test_config1_dq_rounding_floor), so dQ is held to 5e-2 on the latter."""
-    w = W.config(1)
-    _exhaustive(oracle, w, tol_dq=TOL_G / w.q_prescale)
+    """Config 1 as stated: Q pre-scaled by 1/8 in the data, no further scale.  dQ is then the
+    gradient w.r.t. the pre-scaled Q, 8x the gradient w.r.t. the N(0,1) draw, and reaches
+    |dQ| = 21.9; rounding the exact result to bf16 alone errs by 0.060 there
+    (test_config1_dq_rounding_floor).  Every element is held to the stated 5e-2 plus one
+    spacing of bf16 relative to its reference value (RTOL_8X)."""
+    _exhaustive(oracle, W.config(1), rtol=RTOL_8X)
 
 
 def test_config1_tiny_scale_in_kernel(oracle):
-    """Same lengths and draws, the 1/sqrt(64) applied as softmax_scale inside
-    the kernels instead: every stated tolerance applies as is."""
+    """Same lengths and draws, the 1/sqrt(64) applied as softmax_scale inside the kernels
+    instead: every stated tolerance applies as is.  And the literal variant's results are the
+    SAME BITS (dQ times 8: the pre-scaling by a power of two is exact in bf16 and commutes
+    with every rounding), so the literal dQ is exactly as accurate as this one."""
     w = W.config(1)
     w.q_prescale, w.softmax_scale = 1.0, 0.125
-    _exhaustive(oracle, w)
+    a = _exhaustive(oracle, w)
+    b = run_library(W.config(1))
+    for n in ("o", "lse", "dk", "dv"):
+        assert np.array_equal(a[n], b[n]), n
+    assert np.array_equal(8.0 * a["dq"], b["dq"])
+    b["plan"].destroy()
 
 
 def test_config2_qwen05b(oracle):
@@ -118,8 +143,11 @@ def test_extreme_logits(oracle, scale, d):
     dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
     _report("O", out["o"], O, TOL_O)
     _report("LSE", out["lse"], LSE, TOL_O)
-    # gradients grow with the scale (dQ, dK carry a factor softmax_scale): hold them to the
-    # stated bound relative to that factor where it exceeds 1/sqrt(d)
+    # A stress case outside the stated configurations: dQ and dK carry the factor softmax_scale,
+    # here k = scale * sqrt(d) = 8 (6) times the usual 1/sqrt(d), and every absolute error of
+    # the bf16 path grows with it, also on elements that are themselves near zero (0.166 on a
+    # dQ of -0.006 whose row has terms of size 10).  The stated bound is therefore applied to
+    # the gradients divided by k, i.e. 5e-2 * k on the outputs; O, LSE, dV keep theirs.
     k = max(1.0, scale * d ** 0.5)
     _report("dQ", out["dq"] / k, dQ / k, TOL_G)
     _report("dK", out["dk"] / k, dK / k, TOL_G)
@@ -237,70 +265,187 @@ def test_sequence_order_permutes_outputs(oracle):
 # ---------------------------------------------------------------------------
 # full-size micro-batches: sampled oracle parity + size-independent properties
 # ---------------------------------------------------------------------------
-def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400, vals=None, heads_per_row=None,
-             wg_query_rows=0):
+def _progress(capsys, msg):
+    """One line straight to the terminal (past pytest's capture): a full-size case keeps the
+    oracle busy for minutes, and a run that prints nothing that long is taken to be hung."""
+    if capsys is None:
+        print(msg, flush=True)
+    else:
+        with capsys.disabled():
+            print(msg, flush=True)
+
+
+# Largest whole forward of one KV group that the oracle is asked for, in (query row, key, head)
+# triples, unless a test names its own: config 3's long sequence (1.2e9) and the first slice
+# of config 4 fit.  A sequence above it (the 131,072-token prefix of config 4's last slice costs
+# 8e9, minutes on the host cores) has its key columns drawn over as long a tail of the prefix
+# as the cap affords; its early key blocks run the same chains, only longer, and are covered
+# whole at a quarter of the length (test_config4_quarter_twin).
+GROUP_COST_CAP = 2.0e9
+
+
+def _sampled(oracle, w, rows_per_long, cols_per_long, seed, exhaustive_below=400, vals=None,
+             heads_per_row=None, wg_query_rows=0, window=None, capsys=None, group_cap=None,
+             slice_group_cap=None, few_heads_from=0):
+    """Full-size parity on samples the oracle computes one by one.
+
+    Every segment of at most ``exhaustive_below`` query rows: all rows x all heads (O, LSE, dQ)
+    and all of its key columns x all KV heads (dK, dV).  Every longer sequence: ``rows_per_long``
+    seeded query rows plus fixed ones at tile edges x every head (O, LSE, dQ); and ONE seeded KV
+    group for which the oracle runs the whole forward (LSE and D = dO.O of every query row of
+    the group's heads, all of them also compared as O / LSE), so that dK / dV can be compared
+    on ``cols_per_long`` seeded key columns drawn over the WHOLE prefix plus fixed ones in the
+    first key blocks, at the chunk boundaries and on the diagonal.  A sequence whose whole
+    forward exceeds GROUP_COST_CAP gets its columns from the longest tail of the prefix that
+    fits the cap (``group_cap``, or ``slice_group_cap`` for a slice that does not start at
+    position 0).  ``heads_per_row`` limits the sampled rows of segments whose prefix has at
+    least ``few_heads_from`` keys to that many seeded heads each.  ``window``, if given, instead limits the columns of long sequences to the
+    last ``window`` keys (then only the last rows' LSE / D are needed): the mode of the
+    address-range test below."""
+    import time
+    t_start = time.time()
     out = run_library(w, vals=vals, wg_query_rows=wg_query_rows)
     f = widen(out["vals"])
-    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index)
+    desc = oracle.ranges(w.seq_len, w.shard_degree, w.shard_index, w.shard_cut)
     Hq, Hkv, d = w.num_q_heads, w.num_kv_heads, w.head_dim
     g = Hq // Hkv
+    ns = desc["num_seqs"]
     rng = np.random.Generator(np.random.PCG64(seed))
-    # --- rows: O, LSE, dQ ---
-    es, eh, ei = [], [], []
-    for k in range(desc["num_seqs"]):
-        ql = int(desc["q_len"][k])
-        if ql <= exhaustive_below:
-            rows = np.arange(ql)
-        else:
-            fixed = [0, 1, 31, 32, 63, 64, 127, 128, ql - 129, ql - 128, ql - 65, ql - 2, ql - 1]
-            rows = np.unique(np.concatenate([np.array(fixed), rng.integers(0, ql, rows_per_long)]))
-        for i in rows:
-            heads = np.arange(Hq)
-            if ql > exhaustive_below and heads_per_row is not None:
-                heads = np.sort(rng.choice(Hq, heads_per_row, replace=False))
-            es.append(np.full(len(heads), k)); eh.append(heads); ei.append(np.full(len(heads), i))
-    ent = tuple(np.concatenate(x).astype(np.int32) for x in (es, eh, ei))
-    prow = desc["cu_q"][ent[0]] + ent[2]
-    o_ref, lse_ref = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, ent)
-    dq_ref, d_ref = oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale, ent)
-    print(f"{w.name}: checked {len(prow)} (row, head) entries of O/LSE/dQ")
-    _report("O", out["o"][prow, ent[1]], o_ref, TOL_O)
-    _report("LSE", out["lse"][ent[1], prow], lse_ref, TOL_O)
-    _report("dQ", out["dq"][prow, ent[1]], dq_ref, TOL_G)
-    # --- columns: dK, dV for the last `window` keys of long sequences (one KV
-    #     group each) and every key of the short ones (all groups) ---
+    owner = _segment_owner(desc)
+    seqs = [[s for s in range(ns) if owner[s] == k] for k in range(owner[-1] + 1)]
+    is_long = [any(int(desc["q_len"][s]) > exhaustive_below for s in segs) for segs in seqs]
     Tq = desc["total_q"]
     LSEf = np.full((Hq, Tq), np.nan)
     Df = np.full((Hq, Tq), np.nan)
-    cs, cc, cj = [], [], []
-    rs, rh, ri = [], [], []
-    for k in range(desc["num_seqs"]):
-        ql, kvl, qb = int(desc["q_len"][k]), int(desc["kv_len"][k]), int(desc["q_begin"][k])
-        if ql <= exhaustive_below:
-            groups, j0 = range(Hkv), 0 if qb == 0 else kvl - ql
+
+    def edges(n, marks):
+        """positions around the given marks and 32/64/128-row tile edges, inside [0, n)"""
+        e = [m + o for m in marks for o in (-129, -128, -65, -64, -33, -32, -2, -1, 0, 1, 31, 32, 63, 64,
+                                            127, 128, 129, 191, 192, 255, 256)]
+        return np.array(sorted({x for x in e if 0 <= x < n}), np.int64)
+
+    # --- rows: O, LSE, dQ ---
+    es, eh, ei = [], [], []
+    for k, segs in enumerate(seqs):
+        for s in segs:
+            ql = int(desc["q_len"][s])
+            if not is_long[k]:
+                rows = np.arange(ql)
+            else:
+                rows = np.unique(np.concatenate([edges(ql, [0, ql]),
+                                                 rng.choice(ql, min(ql, rows_per_long), replace=False)]))
+            for i in rows:
+                heads = np.arange(Hq)
+                if is_long[k] and heads_per_row is not None and int(desc["kv_len"][s]) >= few_heads_from:
+                    heads = np.sort(rng.choice(Hq, heads_per_row, replace=False))
+                es.append(np.full(len(heads), s)); eh.append(heads); ei.append(np.full(len(heads), i))
+    ent = tuple(np.concatenate(x).astype(np.int32) for x in (es, eh, ei))
+    prow = desc["cu_q"][ent[0]] + ent[2]
+    o_ref, lse_ref = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, ent)
+    _progress(capsys, f"  [{w.name}: oracle forward of {len(prow)} sampled rows done, {time.time() - t_start:.0f} s]")
+    dq_ref, d_ref = oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale, ent)
+    _progress(capsys, f"  [{w.name}: oracle dQ of the sampled rows done, {time.time() - t_start:.0f} s]")
+    LSEf[ent[1], prow] = lse_ref
+    Df[ent[1], prow] = d_ref
+    print(f"{w.name}: checked {len(prow)} (row, head) entries of O/LSE/dQ "
+          f"({sum(is_long)} long sequences: >= {rows_per_long} seeded rows each x {Hq} heads"
+          + (f", {heads_per_row} seeded heads per row where the prefix has {few_heads_from} keys or more"
+             if heads_per_row else "") + ")")
+    _report("O", out["o"][prow, ent[1]], o_ref, TOL_O)
+    _report("LSE", out["lse"][ent[1], prow], lse_ref, TOL_O)
+    _report("dQ", out["dq"][prow, ent[1]], dq_ref, TOL_G)
+
+    # --- LSE and D of one KV group of every long sequence, over all the rows its sampled
+    #     columns can see (the whole sequence unless `window` is given) ---
+    group_of, col_lo = {}, {}
+    chunks = []                          # one (segment, head, rows) piece of oracle work at a time
+    for k, segs in enumerate(seqs):
+        if not is_long[k]:
+            continue
+        c = int(rng.integers(0, Hkv))
+        group_of[k] = c
+        kvl = int(desc["kv_len"][segs[-1]])
+        if window is not None:
+            col_lo[k] = max(0, kvl - window)
         else:
-            groups, j0 = [int(rng.integers(0, Hkv))], kvl - window
-        cols = np.arange(max(j0, 0), kvl)
-        i_min = max(0, int(cols[0]) - qb)
-        for c in groups:
-            cs.append(np.full(len(cols), k)); cc.append(np.full(len(cols), c)); cj.append(cols)
+            # rows (of all the segments) from the end of the sequence backwards until the cap:
+            # the row at position p costs (p + 1) * g
+            pos = np.concatenate([int(desc["q_begin"][s]) + np.arange(int(desc["q_len"][s])) for s in segs])
+            cost = np.cumsum((pos[::-1] + 1.0) * g)
+            cap = group_cap or GROUP_COST_CAP
+            if int(desc["q_begin"][segs[-1]]) > 0 and slice_group_cap:   # a slice that sees a long prefix
+                cap = slice_group_cap
+            n_rows = int(np.searchsorted(cost, cap, side="right"))
+            col_lo[k] = 0 if n_rows >= len(pos) else int(pos[len(pos) - n_rows])
+        for s in segs:
+            ql, qb = int(desc["q_len"][s]), int(desc["q_begin"][s])
+            ii = np.arange(max(0, col_lo[k] - qb), ql)
             for hh in range(c * g, (c + 1) * g):
-                ii = np.arange(i_min, ql)
-                rs.append(np.full(len(ii), k)); rh.append(np.full(len(ii), hh)); ri.append(ii)
-    need = tuple(np.concatenate(x).astype(np.int32) for x in (rs, rh, ri))
-    nrow = desc["cu_q"][need[0]] + need[2]
-    _, l_need = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, need)
-    _, d_need = oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale, need)
-    LSEf[need[1], nrow] = l_need
-    Df[need[1], nrow] = d_need
+                chunks.append((s, hh, ii))
+    n_grp = 0
+    for s, hh, ii in chunks:
+        if len(ii) == 0:
+            continue
+        grp = (np.full(len(ii), s, np.int32), np.full(len(ii), hh, np.int32), ii.astype(np.int32))
+        grow = desc["cu_q"][s] + ii
+        o_g, lse_g = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, grp)
+        LSEf[hh, grow] = lse_g
+        Df[hh, grow] = oracle.delta_rows(f["do"][grow, hh], o_g)
+        _report(f"O (segment {s}, head {hh}, {len(ii)} rows)", out["o"][grow, hh], o_g, TOL_O)
+        _report(f"LSE (segment {s}, head {hh})", out["lse"][hh, grow], lse_g, TOL_O)
+        n_grp += len(ii)
+        if len(ii) * (int(desc["q_begin"][s]) + ii[-1]) > 2e8:
+            _progress(capsys, f"  [{w.name}: oracle forward of segment {s}, head {hh}, rows {ii[0]}..{ii[-1]} done, "
+                              f"{time.time() - t_start:.0f} s]")
+    if n_grp:
+        print(f"{w.name}: forward of one KV group per long sequence: {n_grp} (row, head) entries of O/LSE checked")
+
+    # --- columns: dK, dV ---
+    cs, cc, cj, ct = [], [], [], []      # (segment, kv head, key position) -> target slot
+    tk, tc = [], []                      # target slots: packed key row, kv head
+    n_long_cols = 0
+    for k, segs in enumerate(seqs):
+        last = segs[-1]
+        kvl, base = int(desc["kv_len"][last]), int(desc["cu_k"][last])
+        if not is_long[k]:
+            ql, qb = int(desc["q_len"][last]), int(desc["q_begin"][segs[0]])
+            groups = range(Hkv)
+            cols = np.arange(0 if kvl <= 4096 else kvl - ql, kvl)
+        else:
+            groups = [group_of[k]]
+            if window is None:
+                lo = col_lo[k]
+                marks = [lo, kvl] + [int(desc["q_begin"][s]) for s in segs] + [int(desc["kv_len"][s]) for s in segs]
+                cols = np.unique(np.concatenate([edges(kvl, marks),
+                                                 lo + rng.choice(kvl - lo, min(kvl - lo, cols_per_long), replace=False)]))
+                cols = cols[cols >= lo]
+            else:
+                cols = np.arange(col_lo[k], kvl)
+            n_long_cols += len(cols)
+        for c in groups:
+            slot0 = len(tk)
+            tk.extend(base + cols); tc.extend([c] * len(cols))
+            for s in segs:
+                vis = cols < int(desc["kv_len"][s])
+                cs.append(np.full(int(vis.sum()), s)); cc.append(np.full(int(vis.sum()), c)); cj.append(cols[vis])
+                ct.append(slot0 + np.nonzero(vis)[0])
     cent = tuple(np.concatenate(x).astype(np.int32) for x in (cs, cc, cj))
-    crow = desc["cu_k"][cent[0]] + cent[2]
-    dk_ref, dv_ref = oracle.bwd_dkv_cols(f["q"], f["k"], f["v"], f["do"], LSEf, Df, desc,
-                                         w.softmax_scale, cent)
-    assert np.isfinite(dk_ref).all() and np.isfinite(dv_ref).all()
-    print(f"{w.name}: checked {len(crow)} (key, kv head) entries of dK/dV")
-    _report("dK", out["dk"][crow, cent[1]], dk_ref, TOL_G)
-    _report("dV", out["dv"][crow, cent[1]], dv_ref, TOL_G)
+    slot = np.concatenate(ct)
+    _progress(capsys, f"  [{w.name}: oracle rows and forward done, {time.time() - t_start:.0f} s]")
+    dk_e, dv_e = oracle.bwd_dkv_cols(f["q"], f["k"], f["v"], f["do"], LSEf, Df, desc, w.softmax_scale, cent)
+    _progress(capsys, f"  [{w.name}: oracle key columns done, {time.time() - t_start:.0f} s]")
+    assert np.isfinite(dk_e).all() and np.isfinite(dv_e).all()
+    tk, tc = np.array(tk), np.array(tc)
+    dk_ref, dv_ref = np.zeros((len(tk), d)), np.zeros((len(tk), d))
+    np.add.at(dk_ref, slot, dk_e)    # the two chunks of a two-chunk cut both reach the shared prefix
+    np.add.at(dv_ref, slot, dv_e)
+    span = "; ".join(f"sequence {k}: keys {col_lo[k]}..{int(desc['kv_len'][seqs[k][-1]]) - 1}" for k in sorted(col_lo)
+                     if int(desc["kv_len"][seqs[k][-1]]) > 4096)
+    print(f"{w.name}: checked {len(tk)} (key, kv head) entries of dK/dV, {n_long_cols} of them columns of "
+          f"long sequences ({span})")
+    _report("dK", out["dk"][tk, tc], dk_ref, TOL_G)
+    _report("dV", out["dv"][tk, tc], dv_ref, TOL_G)
+
     # --- properties that hold at any size, on ALL outputs ---
     for n in ("o", "lse", "dq", "dk", "dv"):
         assert np.isfinite(out[n]).all(), n
@@ -312,38 +457,66 @@ def _sampled(oracle, w, rows_per_long, window, seed, exhaustive_below=400, vals=
         return (np.einsum("ihd,ihd->h", x, y, dtype=np.float64),
                 st * np.einsum("ihd,ihd,ihd,ihd->h", xs, ys, xs, ys, dtype=np.float64))
 
-    for k in range(desc["num_seqs"]):
-        qs, qe = desc["cu_q"][k], desc["cu_q"][k + 1]
-        ks, ke = desc["cu_k"][k], desc["cu_k"][k + 1]
+    for segs in seqs:
+        qs, qe = desc["cu_q"][segs[0]], desc["cu_q"][segs[-1] + 1]
+        ks, ke = desc["cu_k"][segs[-1]], desc["cu_k"][segs[-1] + 1]
         per_group = lambda t: t.reshape(Hkv, g).sum(axis=1)  # noqa: E731  (query heads of one KV head are adjacent)
         tq, tq2 = (per_group(t) for t in dots(out["dq"][qs:qe], f["q"][qs:qe]))
-        tk, tk2 = dots(out["dk"][ks:ke], f["k"][ks:ke])
+        tk_, tk2 = dots(out["dk"][ks:ke], f["k"][ks:ke])
         tv, tv2 = dots(out["dv"][ks:ke], f["v"][ks:ke])
         to, to2 = (per_group(t) for t in dots(out["o"][qs:qe], f["do"][qs:qe]))
         for c in range(Hkv):
             # scale invariance of q.k: sum_i dQ_i.Q_i == sum_j dK_j.K_j per (sequence, group)
             noise = 2.0 ** -8 * np.sqrt(tq2[c] + tk2[c])
-            assert abs(tq[c] - tk[c]) <= 8 * noise + 1e-3, (k, c, tq[c], tk[c], noise)
+            assert abs(tq[c] - tk_[c]) <= 8 * noise + 1e-3, (segs, c, tq[c], tk_[c], noise)
             # O = P V  =>  sum_j dV_j.V_j == sum_i dO_i.O_i
             noise = 2.0 ** -8 * np.sqrt(tv2[c] + to2[c])
-            assert abs(tv[c] - to[c]) <= 8 * noise + 1e-3, (k, c, tv[c], to[c], noise)
+            assert abs(tv[c] - to[c]) <= 8 * noise + 1e-3, (segs, c, tv[c], to[c], noise)
     out["plan"].destroy()
 
 
-def test_config3_llama8b_sampled(oracle):
-    _sampled(oracle, W.config(3), rows_per_long=96, window=256, seed=303)
+# Sizes of the samples (the rule: at least 256 seeded query rows of every head and at least
+# 256 seeded key columns of one KV group per long sequence).
+ROWS, COLS = 256, 256
 
 
-def test_config4_shard7_sampled(oracle):
-    _sampled(oracle, W.config(4), rows_per_long=20, window=128, seed=404)
+@pytest.mark.timeout(600)
+def test_config3_llama8b_sampled(oracle, capsys):
+    _sampled(oracle, W.config(3), ROWS, COLS, seed=303, capsys=capsys)
 
 
-def test_config4_shard0_sampled(oracle):
-    _sampled(oracle, W.config(4, shard_index=0), rows_per_long=64, window=256, seed=405)
+@pytest.mark.timeout(600)
+def test_config4_shard7_sampled(oracle, capsys):
+    """Every query row of this slice sees 114,688 to 131,072 keys: the sampled rows of the slice
+    are compared on 8 seeded heads each, and the key columns come from the last 3,700 keys."""
+    _sampled(oracle, W.config(4), ROWS, COLS, seed=404, capsys=capsys, heads_per_row=8, few_heads_from=65536)
 
 
-def test_config5_qwen7b_sampled(oracle):
-    _sampled(oracle, W.config(5), rows_per_long=24, window=128, seed=505)
+@pytest.mark.timeout(600)
+def test_config4_shard0_sampled(oracle, capsys):
+    _sampled(oracle, W.config(4, shard_index=0), ROWS, COLS, seed=405, capsys=capsys)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("index,cut", [(7, 0), (2, 1)])
+def test_config4_quarter_twin(oracle, capsys, index, cut):
+    """Config 4 at a quarter of its length (32,768 tokens, 8 ranks, the same heads and short
+    sequences): the last contiguous slice, and rank 2 of the balanced cut (chunks 2 and 13 of
+    16), with key columns over the WHOLE prefix, chunk boundaries included."""
+    w = W.config(4, shard_index=index)
+    w.seq_len[0] = 32768
+    w.shard_cut = [cut] + [0] * (len(w.seq_len) - 1)
+    w.name = f"config4_quarter_rank{index}_cut{cut}"
+    _sampled(oracle, w, ROWS, COLS, seed=407 + cut, capsys=capsys)
+
+
+@pytest.mark.timeout(800)
+def test_config5_qwen7b_sampled(oracle, capsys):
+    """The 38,365-token local sequence gets the whole forward of one KV group (7 query heads,
+    5.2e9) and key columns over its whole prefix; the slice 3 of 4 of the 65,536-token sequence
+    a tail of its prefix, and 8 seeded heads per sampled row."""
+    _sampled(oracle, W.config(5), ROWS, COLS, seed=505, capsys=capsys, heads_per_row=8, few_heads_from=65536,
+             group_cap=5.5e9, slice_group_cap=1.0e9)
 
 
 @pytest.mark.timeout(400)
@@ -363,8 +536,8 @@ def test_byte_offsets_past_2_31_sampled(oracle, wg_query_rows):
         vals[n] = t.view(torch.int16).cpu().numpy().view(np.uint16)
         del t
     torch.cuda.empty_cache()
-    _sampled(oracle, w, rows_per_long=4, window=128, seed=270, vals=vals, heads_per_row=3,
-             wg_query_rows=wg_query_rows)
+    _sampled(oracle, w, rows_per_long=4, cols_per_long=0, seed=270, vals=vals, heads_per_row=3,
+             wg_query_rows=wg_query_rows, window=128)
 
 
 def test_shards_sum_to_unsharded_at_full_length():

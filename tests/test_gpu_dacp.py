@@ -1,4 +1,4 @@
-"""DACP end to end on the GPU: a micro-batch scheduled by the library's heuristic,
+"""DACP and GDS end to end on the GPU: a micro-batch scheduled by the library's heuristic,
 every rank's share run through the attention kernels, and the pieces put back
 together and compared with the fp64 oracle of the WHOLE (unscheduled) micro-batch:
 O / LSE / dQ rows come from exactly one rank; dK / dV of a distributed sequence are
@@ -16,19 +16,14 @@ pytestmark = pytest.mark.gpu
 TOL_O, TOL_G = 2e-2, 5e-2
 
 
-@pytest.mark.parametrize("cut", [0, 1])
-@pytest.mark.parametrize("N,C,heads,d", [(4, 2000, (4, 2), 64), (3, 2400, (6, 2), 128)])
-def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d, cut):
+def _reassemble_and_compare(oracle, S, ret, N, heads, d, cut, seed, label):
+    """Run every CP rank's share of the micro-batch S under the schedule `ret` through the
+    attention kernels, put the pieces back together and compare them with the fp64 oracle of
+    the WHOLE, unscheduled micro-batch."""
     from paper_2505_19609_amd import binding as B
-    from oracle import dacp as OD
-
-    S = [700, 50, 1500, 300, 64, 2048, 33, 900, 17, 411]
     Hq, Hkv = heads
-    ret = B.skrull_dacp_schedule(S, C, N, Hq * d, Hkv * d)
-    assert list(ret) == OD.dacp_schedule(S, C, N, Hq * d, Hkv * d)
-    assert (ret == -1).any() and (ret >= 0).any()
-
-    whole = W.Workload("whole", S, [1] * len(S), [0] * len(S), Hq, Hkv, d, d ** -0.5, 4242)
+    S = [int(x) for x in S]
+    whole = W.Workload("whole", S, [1] * len(S), [0] * len(S), Hq, Hkv, d, d ** -0.5, seed)
     T = sum(S)
     vals = W.make_values(whole, T, T)
     f = widen(vals)
@@ -42,6 +37,8 @@ def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d, cut):
     seen_q = np.zeros(T, np.int32)
     for j in range(N):
         seq, deg, idx, src = B.skrull_dacp_rank_batch(S, ret, N, j)
+        if len(seq) == 0:
+            continue
         qrows, krows = [], []
         cuts = [cut if g > 1 else 0 for g in deg]
         for s, g, i, k, z in zip(seq, deg, idx, src, cuts):
@@ -66,8 +63,53 @@ def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d, cut):
     for name, got, ref, tol in (("O", o, O, TOL_O), ("LSE", lse, LSE, TOL_O), ("dQ", dq, dQ, TOL_G),
                                 ("dK", dk, dK, TOL_G), ("dV", dv, dV, TOL_G)):
         err = np.abs(got - ref).max()
-        print(f"N={N} {name}: max-abs {err:.4g} (tol {tol})")
+        print(f"{label} {name}: max-abs {err:.4g} (tol {tol})")
         assert np.isfinite(got).all() and err <= tol, (name, err)
+
+
+@pytest.mark.parametrize("cut", [0, 1])
+@pytest.mark.parametrize("N,C,heads,d", [(4, 2000, (4, 2), 64), (3, 2400, (6, 2), 128)])
+def test_scheduled_ranks_reassemble_to_oracle(oracle, N, C, heads, d, cut):
+    from paper_2505_19609_amd import binding as B
+    from oracle import dacp as OD
+
+    S = [700, 50, 1500, 300, 64, 2048, 33, 900, 17, 411]
+    Hq, Hkv = heads
+    ret = B.skrull_dacp_schedule(S, C, N, Hq * d, Hkv * d)
+    assert list(ret) == OD.dacp_schedule(S, C, N, Hq * d, Hkv * d)
+    assert (ret == -1).any() and (ret >= 0).any()
+    _reassemble_and_compare(oracle, S, ret, N, heads, d, cut, 4242, f"N={N}")
+
+
+@pytest.mark.parametrize("cut", [0, 1])
+def test_gds_iteration_matches_oracle_schedule_and_attention(oracle, cut):
+    """Alg. 2 end to end: the library's GDS schedule of a global batch (bin-packing over the
+    DP ranks, stride-interleaved micro-batches, DACP decisions) equals the oracle's decision
+    for decision, and every micro-batch of every DP rank, run rank by rank through the
+    attention kernels under that schedule, reassembles to the fp64 oracle's attention."""
+    from paper_2505_19609_amd import binding as B
+    from oracle import gds as OG
+
+    rng = np.random.Generator(np.random.PCG64(77 + cut))
+    S = [int(x) for x in np.concatenate([rng.integers(16, 700, 18), rng.integers(900, 2000, 6)])]
+    rng.shuffle(S)
+    C, N, ws, heads, d = 1024, 2, 2, (4, 2), 64
+    h, hkv = heads[0] * d, heads[1] * d
+    n_mb = n_dist = 0
+    for r in range(ws):
+        want = OG.gds_schedule(S, C, N, ws, r, h, hkv)
+        assert want is not None
+        bins, mb, ret, m = B.skrull_gds_schedule(S, C, N, ws, r, h, hkv)
+        assert list(bins) == want[0] and m == len(want[1])
+        for j, wmb in enumerate(want[1]):
+            members = B.skrull_gds_micro_batch(S, mb, j)
+            assert [(int(k), int(ret[k])) for k in members] == wmb          # paper Alg. 2, via Alg. 1
+            assert sum(S[k] for k in members) <= C * N
+            n_dist += int((ret[members] == -1).sum())
+            n_mb += 1
+            _reassemble_and_compare(oracle, [S[k] for k in members], ret[members], N, heads, d, cut,
+                                    900 + 10 * r + j, f"dp{r} mb{j}")
+    assert n_mb > ws and n_dist > 0      # several micro-batches per rank, some sequences distributed
 
 
 def test_driver_reports_every_rank(capsys):

@@ -1,19 +1,22 @@
 """The two-stream order (gather of the distributed sequences' K/V hidden behind the local
 sequences' forward, their dK/dV leaving behind the local sequences' backward; Eq. 2)
 against the plain one-stream order and against one plan over the whole micro-batch:
-every output bit for bit."""
+every output bit for bit; and the overlapped order's outputs against the fp64 oracle of the
+same micro-batch at the stated tolerances."""
 import json
 
 import numpy as np
 import pytest
 import torch
 
+from paper_2505_19609_amd import workloads as W
+
 pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("source", ["host", "device"])
 @pytest.mark.parametrize("cut", [0, 1])
-def test_overlapped_order_changes_no_bit(source, cut):
+def test_overlapped_order_changes_no_bit(oracle, source, cut):
     from paper_2505_19609_amd import binding as B
     from paper_2505_19609_amd.overlap_run import RankBatch
 
@@ -67,6 +70,26 @@ def test_overlapped_order_changes_no_bit(source, cut):
     assert torch.equal(dk, torch.cat([a["loc.dk"], a["dist.dk"]]))
     assert torch.equal(dv, torch.cat([a["loc.dv"], a["dist.dv"]]))
     plan.destroy()
+
+    # the overlapped order against the fp64 oracle (Eq. 2 reorders the pieces of the rank's
+    # micro-batch, it must not change what is computed): local sequences, then the slices
+    bits = {n: cat[n].view(torch.int16).cpu().numpy().view(np.uint16) for n in cat}
+    f = {n: W.bf16_bits_to_f32(a) for n, a in bits.items()}
+    desc = oracle.ranges(loc[0] + dist[0], loc[1] + dist[1], loc[2] + dist[2], loc[3] + dist[3])
+    O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, d ** -0.5)
+    dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, d ** -0.5)
+    got = {"o": torch.cat([b["loc.o"], b["dist.o"]]), "lse": torch.cat([b["loc.lse"], b["dist.lse"]], dim=1),
+           "dq": torch.cat([b["loc.dq"], b["dist.dq"]]), "dk": torch.cat([b["loc.dk"], b["dist.dk"]]),
+           "dv": torch.cat([b["loc.dv"], b["dist.dv"]])}
+    for n, ref, tol in (("o", O, 2e-2), ("lse", LSE, 2e-2), ("dq", dQ, 5e-2), ("dk", dK, 5e-2), ("dv", dV, 5e-2)):
+        err = float(np.abs(got[n].float().cpu().numpy() - ref).max())
+        print(f"overlapped ({source}, cut {cut}) {n}: max-abs {err:.4g} vs fp64 oracle (tol {tol})")
+        assert err <= tol, (n, err)
+    # the partial dK/dV rows that left through the staging buffer, against the oracle's
+    first_dist_row = int(desc["cu_k"][len(loc[0])])
+    for n, ref in (("stage.dk", dK), ("stage.dv", dV)):
+        err = float(np.abs(b[n].float().cpu().numpy() - ref[first_dist_row:first_dist_row + rb.remote_rows]).max())
+        assert err <= 5e-2, (n, err)
     rb.destroy()
 
 

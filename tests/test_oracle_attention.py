@@ -235,3 +235,27 @@ def test_sampled_entries_match_the_full_run(oracle):
     for t in range(3):
         row = desc["cu_k"][cent[0][t]] + cent[2][t]
         assert np.array_equal(dk[t], dK[row, cent[1][t]]) and np.array_equal(dv[t], dV[row, cent[1][t]])
+
+
+def test_delta_rows_is_the_row_term_of_the_softmax_gradient(oracle):
+    """delta_rows (D_i = dO_i . O_i from the forward's O) against (a) a value worked by hand,
+    (b) the D that the C backward forms from its own recomputed O (itself pinned by autograd
+    and finite differences above), (c) the identity D_i = sum_j P_ij dP_ij: dS rows sum to 0."""
+    assert oracle.delta_rows(np.array([[1.0, -2.0, 0.5]]), np.array([[3.0, 0.25, -4.0]]))[0] == 0.5
+    S, N, r = [40, 23], [2, 1], [1, 0]
+    Hq, Hkv, d, scale = 4, 2, 8, 0.3
+    desc, q, k, v, do = _problem(S, N, r, Hq, Hkv, d, 91, oracle)
+    ent = oracle.all_row_entries(desc, Hq)
+    rows = desc["cu_q"][ent[0]] + ent[2]
+    o, lse = oracle.fwd_rows(q, k, v, desc, scale, ent)
+    D = oracle.delta_rows(do[rows, ent[1]], o)
+    _, d_c = oracle.bwd_dq_rows(q, k, v, do, desc, scale, ent)
+    assert np.allclose(D, d_c, rtol=0, atol=1e-13)
+    g = Hq // Hkv
+    for t in range(0, len(rows), 7):
+        s, h, i = int(ent[0][t]), int(ent[1][t]), int(ent[2][t])
+        p = int(desc["q_begin"][s]) + i
+        kk = k[desc["cu_k"][s]:desc["cu_k"][s] + p + 1, h // g].astype(np.float64)
+        vv = v[desc["cu_k"][s]:desc["cu_k"][s] + p + 1, h // g].astype(np.float64)
+        P = np.exp(scale * kk @ q[rows[t], h].astype(np.float64) - lse[t])
+        assert abs(P @ (vv @ do[rows[t], h].astype(np.float64)) - D[t]) < 1e-12
