@@ -265,6 +265,23 @@ def test_sequence_order_permutes_outputs(oracle):
 # ---------------------------------------------------------------------------
 # full-size micro-batches: sampled oracle parity + size-independent properties
 # ---------------------------------------------------------------------------
+def _by_kv_head(fn, f, names, desc, scale, ent, g):
+    """oracle.fwd_rows / oracle.bwd_dq_rows on the (segment, head, row) entries `ent`, one KV head
+    at a time on contiguous copies of that head's K and V and of its g query heads.  Only the
+    packing of the inputs changes (a key row is then 4*d bytes from the next instead of
+    4*d*Hkv, which the host's caches and prefetchers like 2-3x better on long prefixes); the
+    oracle does the same arithmetic in the same order and returns the same bits."""
+    a = np.zeros((len(ent[0]), f["q"].shape[2]))
+    b = np.zeros(len(ent[0]))
+    for c in np.unique(ent[1] // g):
+        sel = np.nonzero(ent[1] // g == c)[0]
+        sub = (ent[0][sel], (ent[1][sel] - c * g).astype(np.int32), ent[2][sel])
+        args = [np.ascontiguousarray(f[n][:, c * g:(c + 1) * g] if n in ("q", "do") else f[n][:, c:c + 1])
+                for n in names]
+        a[sel], b[sel] = fn(*args, desc, scale, sub)
+    return a, b
+
+
 def _progress(capsys, msg):
     """One line straight to the terminal (past pytest's capture): a full-size case keeps the
     oracle busy for minutes, and a run that prints nothing that long is taken to be hung."""
@@ -341,9 +358,9 @@ def _sampled(oracle, w, rows_per_long, cols_per_long, seed, exhaustive_below=400
                 es.append(np.full(len(heads), s)); eh.append(heads); ei.append(np.full(len(heads), i))
     ent = tuple(np.concatenate(x).astype(np.int32) for x in (es, eh, ei))
     prow = desc["cu_q"][ent[0]] + ent[2]
-    o_ref, lse_ref = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, ent)
+    o_ref, lse_ref = _by_kv_head(oracle.fwd_rows, f, ("q", "k", "v"), desc, w.softmax_scale, ent, g)
     _progress(capsys, f"  [{w.name}: oracle forward of {len(prow)} sampled rows done, {time.time() - t_start:.0f} s]")
-    dq_ref, d_ref = oracle.bwd_dq_rows(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale, ent)
+    dq_ref, d_ref = _by_kv_head(oracle.bwd_dq_rows, f, ("q", "k", "v", "do"), desc, w.softmax_scale, ent, g)
     _progress(capsys, f"  [{w.name}: oracle dQ of the sampled rows done, {time.time() - t_start:.0f} s]")
     LSEf[ent[1], prow] = lse_ref
     Df[ent[1], prow] = d_ref
@@ -388,7 +405,7 @@ def _sampled(oracle, w, rows_per_long, cols_per_long, seed, exhaustive_below=400
             continue
         grp = (np.full(len(ii), s, np.int32), np.full(len(ii), hh, np.int32), ii.astype(np.int32))
         grow = desc["cu_q"][s] + ii
-        o_g, lse_g = oracle.fwd_rows(f["q"], f["k"], f["v"], desc, w.softmax_scale, grp)
+        o_g, lse_g = _by_kv_head(oracle.fwd_rows, f, ("q", "k", "v"), desc, w.softmax_scale, grp, g)
         LSEf[hh, grow] = lse_g
         Df[hh, grow] = oracle.delta_rows(f["do"][grow, hh], o_g)
         _report(f"O (segment {s}, head {hh}, {len(ii)} rows)", out["o"][grow, hh], o_g, TOL_O)
