@@ -209,6 +209,27 @@ int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k
                     void *dq, void *dk, void *dv,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * skrull_attn_bwd for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving or training loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and errors as skrull_attn_bwd (bit for bit: the
+ * same kernels), but the workspace (-D and LSE*log2(e) per query head and row, and the
+ * fp32 partial dK/dV when head_split > 1) is a static device array inside the library of
+ * SKRULL_STATIC_SCRATCH_BYTES bytes per GPU, held from library load until the process
+ * ends; its address on a device is looked up when the first plan is made on that device.
+ * The call allocates and frees nothing, does not synchronise, and only enqueues kernels
+ * on `hip_stream`.  Nothing in the array has to start at zero (every word read was
+ * written by an earlier kernel of the same call).
+ * SKRULL_EINVAL, besides skrull_attn_bwd's cases, when info.bwd_workspace_bytes exceeds
+ * SKRULL_STATIC_SCRATCH_BYTES (strerror names both sizes).
+ * Every call on one GPU uses the same array: calls that may overlap on one GPU (two
+ * streams, two threads) race and must be ordered by the caller.
+ */
+#define SKRULL_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int skrull_attn_bwd_static(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
+                           const void *o, const float *lse, const void *d_o,
+                           void *dq, void *dk, void *dv, void *hip_stream);
+
 /* Release a plan and its device arrays (NULL is ignored). */
 void skrull_attn_plan_destroy(skrull_attn_plan_t *plan);
 

@@ -18,7 +18,7 @@ SKRULL_OK, SKRULL_EINVAL, SKRULL_ENOMEM, SKRULL_EHIP, SKRULL_EUNSUPPORTED, SKRUL
 CUT_CONTIGUOUS, CUT_TWO_CHUNKS = 0, 1
 
 EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
-                    "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_plan_destroy",
+                    "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_bwd_static", "skrull_attn_plan_destroy",
                     "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read",
                     "skrull_attn_mfma_ceiling",
                     "skrull_dacp_schedule", "skrull_dacp_rank_batch",
@@ -89,6 +89,8 @@ def lib():
         L.skrull_attn_fwd.restype = ctypes.c_int
         L.skrull_attn_bwd.argtypes = [vp] * 11 + [ctypes.c_size_t, vp]
         L.skrull_attn_bwd.restype = ctypes.c_int
+        L.skrull_attn_bwd_static.argtypes = [vp] * 11
+        L.skrull_attn_bwd_static.restype = ctypes.c_int
         L.skrull_attn_plan_destroy.argtypes = [vp]
         L.skrull_attn_plan_destroy.restype = None
         L.skrull_attn_strerror.argtypes = [ctypes.c_int]
@@ -207,6 +209,15 @@ def skrull_attn_bwd(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, workspace, str
     _check(lib().skrull_attn_bwd(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
                                  _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def skrull_attn_bwd_static(plan: Plan, q, k, v, o, lse, d_o, dq, dk, dv, stream=None):
+    """skrull_attn_bwd on the library's static workspace (no allocation anywhere)."""
+    _check(lib().skrull_attn_bwd_static(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                        _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _stream_ptr(stream)))
 
 
 def skrull_attn_profile(enable: bool):

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <new>
 
 #include "common.h"
@@ -38,6 +39,28 @@ hipEvent_t g_ev[6];
 bool g_ev_made = false, g_fwd_seen = false, g_bwd_seen = false;
 
 constexpr int32_t kMaxItems = 1 << 20;  // rank-counting sort is quadratic in the item count
+
+// Workspace of skrull_attn_bwd_static, the backward entry point for callers that cannot
+// allocate: one array per GPU that the library runs on, held until the process ends.
+// In host code the array's name is only a stand-in for the symbol; the device address
+// comes from hipGetSymbolAddress, once per device, and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[SKRULL_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on device `dev`, which must be the current device.
+int resolve_scratch(int dev, void **out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return SKRULL_EUNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // (a second thread stores the same address)
+    }
+    *out = p;
+    return SKRULL_OK;
+}
 
 int check_device(int *dev_out, int *compute_units)
 {
@@ -144,6 +167,10 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     int dev = 0, compute_units = 0;
     int rc = check_device(&dev, &compute_units);
     if (rc != SKRULL_OK) return rc;
+    {   // set-up for skrull_attn_bwd_static: this device's address of the static workspace
+        void *unused = nullptr;
+        if ((rc = resolve_scratch(dev, &unused)) != SKRULL_OK) return rc;
+    }
 
     // dK/dV block size when the caller leaves it open.  At head_dim 64 the kernel has a
     // 12-wavefront shape over 192 key rows; with a sequence of 8,192 tokens or more in the
@@ -357,6 +384,33 @@ int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k
     if ((int64_t)workspace_bytes < info.bwd_workspace_bytes) return SKRULL_EINVAL;
     if (int rc = check_plan_device(plan)) return rc;
     hipError_t e = launch_bwd(plan, q, k, v, o, lse, d_o, dq, dk, dv, (float *)workspace,
+                              (hipStream_t)hip_stream, g_profile ? g_ev + 2 : nullptr);
+    if (e != hipSuccess) return hip_fail(e, "backward launch");
+    if (g_profile) g_bwd_seen = true;
+    return SKRULL_OK;
+}
+
+int skrull_attn_bwd_static(const skrull_attn_plan_t *plan, const void *q, const void *k, const void *v,
+                           const void *o, const float *lse, const void *d_o, void *dq, void *dk,
+                           void *dv, void *hip_stream)
+{
+    if (!plan) return SKRULL_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+        misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv))
+        return SKRULL_EINVAL;
+    skrull_attn_plan_info_t info;
+    skrull_attn_plan_info(plan, &info);
+    if (info.bwd_workspace_bytes > (int64_t)SKRULL_STATIC_SCRATCH_BYTES) {
+        snprintf(g_err, sizeof g_err,
+                 "this plan needs %lld bytes of backward workspace, the static one holds %lld "
+                 "(use skrull_attn_bwd, or a plan with head_split = 1 if the partial sums are what is large)",
+                 (long long)info.bwd_workspace_bytes, (long long)SKRULL_STATIC_SCRATCH_BYTES);
+        return SKRULL_EINVAL;
+    }
+    if (int rc = check_plan_device(plan)) return rc;
+    void *ws = nullptr;  // resolved when the plan was made; looked up again only if that was another process state
+    if (int rc = resolve_scratch(plan->device, &ws)) return rc;
+    hipError_t e = launch_bwd(plan, q, k, v, o, lse, d_o, dq, dk, dv, (float *)ws,
                               (hipStream_t)hip_stream, g_profile ? g_ev + 2 : nullptr);
     if (e != hipSuccess) return hip_fail(e, "backward launch");
     if (g_profile) g_bwd_seen = true;
