@@ -26,8 +26,9 @@
  * Query head h reads key/value head h / (num_q_heads / num_kv_heads).
  *
  * Every function returns 0 (SKRULL_OK) or a negative code; nothing throws or
- * aborts, and the only process-wide state is the opt-in profiling switch at
- * the end of this header.  On failure output pointers written
+ * aborts.  State outside the plans: per calling thread, the text of its last error and
+ * the opt-in profiling switch at the end of this header; per GPU, the static workspace
+ * of skrull_attn_bwd_static.  On failure output pointers written
  * through `out` arguments are left untouched.  Every step runs in HIP kernels;
  * there is no CPU fallback.
  */
@@ -144,8 +145,13 @@ enum {
  * `hip_stream` (a hipStream_t, may be NULL for the default stream) carries the
  * kernels; the call synchronises that stream because the totals come back to
  * the host.  *out receives a plan that must be released with
- * skrull_attn_plan_destroy.  A plan is immutable and may be reused by any
- * number of fwd/bwd calls on any stream of the same device.
+ * skrull_attn_plan_destroy.  A plan's descriptor and work lists are immutable and it may
+ * be reused by any number of fwd/bwd calls on any stream of the same device.  The kernels
+ * are persistent (workgroups take work items from queues until none is left, see
+ * skrull_attn_fwd); a backward call keeps its queues in its own workspace, a forward call
+ * takes one of the plan's 64 queue slots in turn, so at most 64 forward calls of one plan
+ * may be in flight at once, and a forward call captured in a HIP graph (which keeps the
+ * slot it was captured with) must not overlap with other forward calls of the same plan.
  * SKRULL_EINVAL: null pointer, K < 1, S_k < 1, degree < 1, index outside
  * [0, degree), more chunks than tokens (degree > S_k, or 2*degree > S_k for a
  * two-chunk cut), a cut other than the two above, head_split outside [0, Hq/Hkv],
@@ -177,7 +183,14 @@ int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst
  * rests on (Sec. 4.2.1; App. B.2, the 4*b*h*S^2 term).  bf16 MFMA products,
  * fp32 accumulation and softmax, O rounded to bf16 (nearest even), LSE fp32.
  * q, k, v (read) and o, lse (written) are DEVICE pointers in the layout above.
- * Only enqueues on `hip_stream`; never synchronises.
+ * Work items go to compute units the way the paper sends sequences to ranks (Alg. 1:
+ * the next piece to argmin of the loads): the launch holds as many workgroups as the chip
+ * runs at once, each takes the next item of the cost-ordered list of its die until that is
+ * empty and then the largest remaining item of the fullest other list (the dies of one chip
+ * differ in speed by several percent, which a fixed deal of workgroups to dies cannot even
+ * out).  Results do not depend on which workgroup took which item.
+ * Only enqueues on `hip_stream` (a small kernel that clears the queue, then the attention
+ * kernel); never synchronises.
  * SKRULL_EINVAL on a null or misaligned pointer, or when the current device is
  * not the one the plan was made on.
  */
@@ -244,18 +257,41 @@ const char *skrull_attn_strerror(int code);
  * most recent forward and backward calls and returns the kernel durations in
  * milliseconds: ms[0] forward, ms[1] always 0 (D = rowsum(dO*O) is formed inside
  * the dQ kernel), ms[2] dK/dV with its reduction, ms[3] dQ
- * (an entry is -1 if that call has not been made since enabling).  One set of
- * events per process: use from one thread, one stream at a time.
+ * (an entry is -1 if that call has not been made since enabling).  The switch and its
+ * events belong to the CALLING THREAD: it affects only calls that thread makes, any
+ * number of threads may profile at once, and a thread reads back what it recorded itself
+ * (one stream at a time per thread).  Disabling releases the thread's events;
+ * skrull_attn_profile_read returns SKRULL_EINVAL on a thread that has not enabled it.
  */
 int skrull_attn_profile(int enable);
 int skrull_attn_profile_read(float ms[4]);
+
+/*
+ * Measurement aid (not part of the method): how evenly the cost-ordered work lists load the
+ * compute units.  After skrull_attn_trace(records, bytes) the calling thread's forward and
+ * backward calls make every workgroup write one 32-byte record into the caller's DEVICE
+ * buffer `records` (16-byte aligned; the caller zeroes it first):
+ *   uint64 t0, t1   the chip-wide 100 MHz counter (s_memrealtime) at its start and end
+ *   uint32 hw_id    the HW_ID register (bits 8-11 compute unit, 12 shader array, 13-15 shader engine)
+ *   uint32 xcc_id   the XCC_ID register (die)
+ *   uint32 block    its blockIdx.x
+ *   uint32 one      1
+ * Records of the forward kernel come first, then the dQ kernel's, then the dK/dV kernel's;
+ * skrull_attn_trace_layout gives, for a plan, the first record and the number of records
+ * (= workgroups; those that leave at once write nothing) of the three.  A call whose records
+ * do not fit `bytes` returns SKRULL_EINVAL.  skrull_attn_trace(NULL, 0) switches it off.
+ * Untraced calls pay one scalar branch per workgroup.  skrull_attn_bwd_static is never traced.
+ */
+int skrull_attn_trace(void *records, size_t bytes);
+int skrull_attn_trace_layout(const skrull_attn_plan_t *plan, int32_t first_record[3], int32_t num_records[3]);
 
 /*
  * Measurement aid (not part of the method).  Runs three launches of about 20 ms of
  * nothing but v_mfma_f32_32x32x16_bf16 on every compute unit (two waves per SIMD,
  * operands in registers) on `hip_stream`, waits, and returns the rate of the last in TFLOP/s: the
  * matrix-pipe ceiling this GPU sustains at the clock it holds under such load, to
- * be read beside the nominal 2.5 PFLOP/s.  Allocates and frees a small scratch buffer.
+ * be read beside the nominal 2.5 PFLOP/s.  Allocates nothing (its 512 KB sink is the start
+ * of the static workspace of skrull_attn_bwd_static: do not overlap the two on one GPU).
  */
 int skrull_attn_mfma_ceiling(void *hip_stream, float *tflops);
 

@@ -20,7 +20,7 @@ CUT_CONTIGUOUS, CUT_TWO_CHUNKS = 0, 1
 EXPORTED_SYMBOLS = ("skrull_attn_plan", "skrull_attn_plan_info", "skrull_attn_plan_export",
                     "skrull_attn_fwd", "skrull_attn_bwd", "skrull_attn_bwd_static", "skrull_attn_plan_destroy",
                     "skrull_attn_strerror", "skrull_attn_profile", "skrull_attn_profile_read",
-                    "skrull_attn_mfma_ceiling",
+                    "skrull_attn_mfma_ceiling", "skrull_attn_trace", "skrull_attn_trace_layout",
                     "skrull_dacp_schedule", "skrull_dacp_rank_batch",
                     "skrull_gds_binpack", "skrull_gds_schedule", "skrull_gds_micro_batch")
 
@@ -102,6 +102,10 @@ def lib():
         L.skrull_attn_mfma_ceiling.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
         L.skrull_attn_mfma_ceiling.restype = ctypes.c_int
         i32p = ctypes.POINTER(ctypes.c_int32)
+        L.skrull_attn_trace.argtypes = [vp, ctypes.c_size_t]
+        L.skrull_attn_trace.restype = ctypes.c_int
+        L.skrull_attn_trace_layout.argtypes = [vp, i32p, i32p]
+        L.skrull_attn_trace_layout.restype = ctypes.c_int
         L.skrull_dacp_schedule.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32,
                                            ctypes.POINTER(FlopsModel), i32p]
         L.skrull_dacp_schedule.restype = ctypes.c_int
@@ -230,6 +234,21 @@ def skrull_attn_profile_read():
     ms = (ctypes.c_float * 4)()
     _check(lib().skrull_attn_profile_read(ms))
     return [float(x) for x in ms]
+
+
+def skrull_attn_trace(records=None):
+    """Switch the per-workgroup trace on (records: a zeroed torch uint8 CUDA tensor) or off (None)."""
+    if records is None:
+        _check(lib().skrull_attn_trace(None, 0))
+    else:
+        _check(lib().skrull_attn_trace(_ptr(records), records.numel() * records.element_size()))
+
+
+def skrull_attn_trace_layout(plan: Plan):
+    """(first_record[3], num_records[3]) of the forward, dQ and dK/dV kernels of `plan`."""
+    first, num = (ctypes.c_int32 * 3)(), (ctypes.c_int32 * 3)()
+    _check(lib().skrull_attn_trace_layout(plan.handle, first, num))
+    return [int(x) for x in first], [int(x) for x in num]
 
 
 def skrull_attn_mfma_ceiling(stream=None) -> float:

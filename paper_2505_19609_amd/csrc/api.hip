@@ -1,6 +1,9 @@
 // Host side of the C ABI: argument validation, plan construction, launches.
-// No arithmetic of the method happens here; the descriptor, the work lists and
-// all attention math are produced by kernels (plan.hip, fwd.hip, bwd.hip).
+// No arithmetic of the method happens here: the descriptor, the work lists, their costs
+// and all attention math are produced by kernels (plan.hip, fwd.hip, bwd.hip).  What the
+// host derives from the lengths are upper bounds only (how many work items there can be at
+// most, for the allocations and grids) and the tuning choices documented in the header,
+// which it takes from the totals that the plan kernels return.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -32,11 +35,20 @@ inline bool misaligned(const void *p) { return p == nullptr || ((uintptr_t)p & 1
 
 inline int64_t align4(int64_t n) { return (n + 3) & ~(int64_t)3; }
 
-// Opt-in kernel timing: events 0/1 bracket the forward kernel, 2..5 delimit the
-// three backward kernels.
-bool g_profile = false;
-hipEvent_t g_ev[6];
-bool g_ev_made = false, g_fwd_seen = false, g_bwd_seen = false;
+// Opt-in kernel timing, per calling thread: events 0/1 bracket the forward kernel, 2..4
+// delimit the backward kernels.  A thread that never enables it owns nothing.
+struct ProfileState {
+    bool on = false, made = false, fwd_seen = false, bwd_seen = false;
+    hipEvent_t ev[6];
+};
+thread_local ProfileState g_prof;
+
+// Opt-in per-workgroup trace, per calling thread: a caller-owned device buffer of WgTrace records.
+struct TraceState {
+    WgTrace *buf = nullptr;
+    size_t records = 0;
+};
+thread_local TraceState g_trace;
 
 constexpr int32_t kMaxItems = 1 << 20;  // rank-counting sort is quadratic in the item count
 
@@ -119,10 +131,7 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     int32_t longest_seq = 0;
     const int64_t q_row_bytes = (int64_t)p->num_q_heads * p->head_dim * 2;
     const int64_t kv_row_bytes = (int64_t)p->num_kv_heads * p->head_dim * 2;
-    int64_t cap_fwd = 0, cap_dkv = 0, cap_dkv_192 = 0;
-    // cost (query blocks of BM rows) of the dK/dV items there would be with 128 key rows:
-    // their sum and maximum, for the choice of block_n below
-    int64_t cost128_sum = 0, cost128_max = 0;
+    int64_t cap_fwd = 0, cap_dkv = 0;
     for (int32_t k = 0; k < K; ++k) {
         const int32_t s = p->seq_len[k], n = p->shard_degree[k], r = p->shard_index[k];
         const int32_t z = p->shard_cut ? p->shard_cut[k] : SKRULL_CUT_CONTIGUOUS;
@@ -141,26 +150,6 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         }
         cap_fwd += (1 + z) * ((longest + BM - 1) / BM);
         cap_dkv += ((int64_t)s + BN - 1) / BN;
-        cap_dkv_192 += ((int64_t)s + 191) / 192;
-        if (p->block_n == 0 && p->head_dim == 64 && s < 8192) {
-            // this rank's one or two chunks [qb, qe) of the sequence; a key block costs the
-            // query blocks of each chunk from the first row at or after the block's first key
-            const int64_t c_lo = r, c_hi = z ? 2 * (int64_t)n - 1 - r : r;
-            const int64_t kv_end = (c_hi + 1) * s / chunks;
-            for (int64_t j0 = 0; j0 < kv_end; j0 += 128) {
-                int64_t cost = 0;
-                for (int64_t c = c_lo;; c = c_hi) {
-                    const int64_t qb = c * s / chunks, qe = (c + 1) * s / chunks;
-                    if (j0 < qe) {
-                        const int64_t i0 = j0 > qb ? j0 - qb : 0;
-                        cost += (qe - qb + BM - 1) / BM - i0 / BM;
-                    }
-                    if (c == c_hi) break;
-                }
-                cost128_sum += cost;
-                cost128_max = cost > cost128_max ? cost : cost128_max;
-            }
-        }
     }
     if (n_seg > INT32_MAX / 2) return SKRULL_EINVAL;
     if (cap_fwd > 8 * (int64_t)kMaxItems || cap_dkv > 8 * (int64_t)kMaxItems) return SKRULL_EINVAL;
@@ -180,17 +169,14 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     // exactly where the work list is so short that the heads are split anyway (longest
     // chain above an even share of 128-key items, see head_split below), and loses 2-25 %
     // where it is not: there the fewer, larger workgroups and the split they then need
-    // cost more than the third wavefront per SIMD brings.
+    // cost more than the third wavefront per SIMD brings.  That second case is decided by the
+    // ranges kernel from the costs of the 128-key work list (bn_alt), and comes back in totals.
+    int32_t bn_alt = 0;
     if (p->block_n == 0 && p->head_dim == 64) {
-        bool take192 = longest_seq >= 8192;
-        if (!take192 && cost128_sum > 0) {
-            take192 = (double)cost128_max > (double)cost128_sum * p->num_kv_heads / compute_units;
-        }
-        if (take192) {
-            BN = 192;
-            cap_dkv = cap_dkv_192;
-        }
+        if (longest_seq >= 8192) BN = 192;
+        else bn_alt = 192;
     }
+    // (cap_dkv counts items of BN key rows; the alternative is larger, so it needs fewer)
 
     hipStream_t st = (hipStream_t)hip_stream;
     skrull_attn_plan_t *plan = nullptr;
@@ -202,6 +188,7 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     const int64_t totals_ints = align4((int64_t)((sizeof(PlanTotals) + 3) / 4));
     const int64_t tmp_ints = 4 * kin + 2 * kpad + totals_ints + 4 * (cap_fwd + cap_dkv);
     const int64_t desc_ints = 6 * kpad;
+    const int64_t queue_ints = SKRULL_FWD_QUEUE_SLOTS * 16;  // 64-byte work queues of the forward launches
     int32_t *fwd_off = nullptr, *dkv_off = nullptr, *scratch = nullptr;
     PlanTotals *totals_d = nullptr;
 
@@ -219,14 +206,15 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     if (p->shard_cut) memcpy(host_in + 3 * kin, p->shard_cut, (size_t)K * 4);
 
     HIP_TRY(hipMalloc((void **)&tmp, (size_t)tmp_ints * sizeof(int32_t)));
-    HIP_TRY(hipMalloc((void **)&plan->pool, (size_t)(desc_ints + 4 * (cap_fwd + cap_dkv)) * sizeof(int32_t)));
-    plan->cu_q = plan->pool;
-    plan->cu_k = plan->pool + kpad;
-    plan->q_begin = plan->pool + 2 * kpad;
-    plan->q_len = plan->pool + 3 * kpad;
-    plan->kv_len = plan->pool + 4 * kpad;
-    plan->shares_kv = plan->pool + 5 * kpad;
-    plan->fwd_items = plan->pool + desc_ints;
+    HIP_TRY(hipMalloc((void **)&plan->pool, (size_t)(queue_ints + desc_ints + 4 * (cap_fwd + cap_dkv)) * sizeof(int32_t)));
+    plan->fwd_queues = (WorkQueue *)plan->pool;   // (zeroed by every forward call before its launch)
+    plan->cu_q = plan->pool + queue_ints;
+    plan->cu_k = plan->cu_q + kpad;
+    plan->q_begin = plan->cu_q + 2 * kpad;
+    plan->q_len = plan->cu_q + 3 * kpad;
+    plan->kv_len = plan->cu_q + 4 * kpad;
+    plan->shares_kv = plan->cu_q + 5 * kpad;
+    plan->fwd_items = plan->cu_q + desc_ints;
     plan->dkv_items = plan->fwd_items + 4 * cap_fwd;
     fwd_off = tmp + 4 * kin;
     dkv_off = fwd_off + kpad;
@@ -238,7 +226,8 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
                                INT32_MAX / (p->num_q_heads * p->head_dim),
                                INT32_MAX / (p->num_kv_heads * p->head_dim), plan->q_begin,
                                plan->q_len, plan->kv_len, plan->cu_q, plan->cu_k, plan->shares_kv,
-                               fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, totals_d, st));
+                               fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, bn_alt, p->num_kv_heads,
+                               compute_units, totals_d, st));
     HIP_TRY(launch_plan_items(plan, fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, scratch,
                               scratch + 4 * cap_fwd, totals_d, st));
     HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
@@ -250,6 +239,8 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         rc = SKRULL_EINVAL;
         goto done;
     }
+    if (totals.block_n != BN && totals.block_n != bn_alt) { rc = SKRULL_EHIP; snprintf(g_err, sizeof g_err, "plan kernels returned block_n %d", totals.block_n); goto done; }
+    plan->BN = totals.block_n;
     plan->total_q = (int32_t)totals.total_q;
     plan->total_k = (int32_t)totals.total_k;
     plan->n_fwd = (int32_t)totals.n_fwd;
@@ -323,7 +314,8 @@ int skrull_attn_plan_info(const skrull_attn_plan_t *plan, skrull_attn_plan_info_
     info->attended_pairs = plan->pairs;
     info->useful_flops_fwd = 4 * plan->pairs * plan->d * plan->Hq;
     info->useful_flops_bwd = 10 * plan->pairs * plan->d * plan->Hq;
-    info->bwd_workspace_bytes = (((int64_t)plan->Hq * plan->total_q * 8) + 255) & ~(int64_t)255;
+    // -D and LSE*log2(e) per (head, row), then 256 bytes for the work queues of the two kernels
+    info->bwd_workspace_bytes = ((((int64_t)plan->Hq * plan->total_q * 8) + 255) & ~(int64_t)255) + 256;
     if (plan->head_split > 1)  // fp32 partial dK and dV of every share of the heads
         info->bwd_workspace_bytes += 2 * (int64_t)plan->head_split * plan->total_k * plan->Hkv * plan->d * 4;
     info->num_segments = plan->NS;
@@ -363,10 +355,15 @@ int skrull_attn_fwd(const skrull_attn_plan_t *plan, const void *q, const void *k
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
         return SKRULL_EINVAL;
     if (int rc = check_plan_device(plan)) return rc;
-    if (g_profile) (void)hipEventRecord(g_ev[0], (hipStream_t)hip_stream);
-    hipError_t e = launch_fwd(plan, q, k, v, o, lse, (hipStream_t)hip_stream);
+    if (g_prof.on) (void)hipEventRecord(g_prof.ev[0], (hipStream_t)hip_stream);
+    WgTrace *trace = nullptr;
+    if (g_trace.buf) {
+        if ((size_t)grid_fwd(plan) > g_trace.records) return SKRULL_EINVAL;
+        trace = g_trace.buf;
+    }
+    hipError_t e = launch_fwd(plan, q, k, v, o, lse, (hipStream_t)hip_stream, trace);
     if (e != hipSuccess) return hip_fail(e, "forward launch");
-    if (g_profile) { (void)hipEventRecord(g_ev[1], (hipStream_t)hip_stream); g_fwd_seen = true; }
+    if (g_prof.on) { (void)hipEventRecord(g_prof.ev[1], (hipStream_t)hip_stream); g_prof.fwd_seen = true; }
     return SKRULL_OK;
 }
 
@@ -383,10 +380,16 @@ int skrull_attn_bwd(const skrull_attn_plan_t *plan, const void *q, const void *k
     skrull_attn_plan_info(plan, &info);
     if ((int64_t)workspace_bytes < info.bwd_workspace_bytes) return SKRULL_EINVAL;
     if (int rc = check_plan_device(plan)) return rc;
+    WgTrace *trace = nullptr;
+    if (g_trace.buf) {  // after the forward's records
+        const size_t first = (size_t)grid_fwd(plan);
+        if (first + grid_dq(plan) + grid_dkv(plan) > g_trace.records) return SKRULL_EINVAL;
+        trace = g_trace.buf + first;
+    }
     hipError_t e = launch_bwd(plan, q, k, v, o, lse, d_o, dq, dk, dv, (float *)workspace,
-                              (hipStream_t)hip_stream, g_profile ? g_ev + 2 : nullptr);
+                              (hipStream_t)hip_stream, g_prof.on ? g_prof.ev + 2 : nullptr, trace);
     if (e != hipSuccess) return hip_fail(e, "backward launch");
-    if (g_profile) g_bwd_seen = true;
+    if (g_prof.on) g_prof.bwd_seen = true;
     return SKRULL_OK;
 }
 
@@ -411,9 +414,9 @@ int skrull_attn_bwd_static(const skrull_attn_plan_t *plan, const void *q, const 
     void *ws = nullptr;  // resolved when the plan was made; looked up again only if that was another process state
     if (int rc = resolve_scratch(plan->device, &ws)) return rc;
     hipError_t e = launch_bwd(plan, q, k, v, o, lse, d_o, dq, dk, dv, (float *)ws,
-                              (hipStream_t)hip_stream, g_profile ? g_ev + 2 : nullptr);
+                              (hipStream_t)hip_stream, g_prof.on ? g_prof.ev + 2 : nullptr, nullptr);
     if (e != hipSuccess) return hip_fail(e, "backward launch");
-    if (g_profile) g_bwd_seen = true;
+    if (g_prof.on) g_prof.bwd_seen = true;
     return SKRULL_OK;
 }
 
@@ -431,46 +434,75 @@ int skrull_attn_mfma_ceiling(void *hip_stream, float *tflops)
     int rc = check_device(&dev, &compute_units);
     if (rc != SKRULL_OK) return rc;
     const int blocks = compute_units, iters = 40000;  // ~20 ms of MFMAs
-    float *scratch = nullptr, ms = 0.0f;
-    hipError_t e = hipMalloc((void **)&scratch, (size_t)blocks * 512 * sizeof(float));
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(probe)");
-    e = run_mfma_probe(blocks, iters, scratch, (hipStream_t)hip_stream, &ms);
-    (void)hipFree(scratch);
+    float ms = 0.0f;
+    void *ws = nullptr;  // the probe's sink (blocks x 2 KB) is the static workspace: nothing is allocated
+    if ((size_t)blocks * 512 * sizeof(float) > (size_t)SKRULL_STATIC_SCRATCH_BYTES) return SKRULL_EUNSUPPORTED;
+    if ((rc = resolve_scratch(dev, &ws)) != SKRULL_OK) return rc;
+    hipError_t e = run_mfma_probe(blocks, iters, (float *)ws, (hipStream_t)hip_stream, &ms);
     if (e != hipSuccess) return hip_fail(e, "MFMA probe");
     // blocks x 8 waves x iters x 4 MFMAs x 32*32*16*2 flop
     *tflops = (float)((double)blocks * 8.0 * iters * 4.0 * 32768.0 / (ms * 1e-3) / 1e12);
     return SKRULL_OK;
 }
 
+int skrull_attn_trace(void *records, size_t bytes)
+{
+    if (records && (misaligned(records) || bytes < sizeof(WgTrace))) return SKRULL_EINVAL;
+    g_trace.buf = (WgTrace *)records;
+    g_trace.records = records ? bytes / sizeof(WgTrace) : 0;
+    return SKRULL_OK;
+}
+
+int skrull_attn_trace_layout(const skrull_attn_plan_t *plan, int32_t first_record[3], int32_t num_records[3])
+{
+    if (!plan || !first_record || !num_records) return SKRULL_EINVAL;
+    num_records[0] = grid_fwd(plan);
+    num_records[1] = grid_dq(plan);
+    num_records[2] = grid_dkv(plan);
+    first_record[0] = 0;
+    first_record[1] = num_records[0];
+    first_record[2] = num_records[0] + num_records[1];
+    return SKRULL_OK;
+}
+
 int skrull_attn_profile(int enable)
 {
-    if (enable && !g_ev_made) {
+    ProfileState &ps = g_prof;
+    if (enable && !ps.made) {
         for (int i = 0; i < 6; ++i) {
-            hipError_t e = hipEventCreate(&g_ev[i]);
-            if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+            hipError_t e = hipEventCreate(&ps.ev[i]);
+            if (e != hipSuccess) {
+                while (i-- > 0) (void)hipEventDestroy(ps.ev[i]);
+                return hip_fail(e, "hipEventCreate");
+            }
         }
-        g_ev_made = true;
+        ps.made = true;
     }
-    g_profile = enable != 0;
-    g_fwd_seen = g_bwd_seen = false;
+    if (!enable && ps.made) {  // switching off releases the thread's events
+        for (int i = 0; i < 6; ++i) (void)hipEventDestroy(ps.ev[i]);
+        ps.made = false;
+    }
+    ps.on = enable != 0;
+    ps.fwd_seen = ps.bwd_seen = false;
     return SKRULL_OK;
 }
 
 int skrull_attn_profile_read(float ms[4])
 {
-    if (!ms || !g_ev_made) return SKRULL_EINVAL;
+    ProfileState &ps = g_prof;
+    if (!ms || !ps.on) return SKRULL_EINVAL;
     for (int i = 0; i < 4; ++i) ms[i] = -1.0f;
     hipError_t e;
-    if (g_fwd_seen) {
-        if ((e = hipEventSynchronize(g_ev[1])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
-        if ((e = hipEventElapsedTime(&ms[0], g_ev[0], g_ev[1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+    if (ps.fwd_seen) {
+        if ((e = hipEventSynchronize(ps.ev[1])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        if ((e = hipEventElapsedTime(&ms[0], ps.ev[0], ps.ev[1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
     }
-    if (g_bwd_seen) {
-        // backward events: g_ev[2] start, g_ev[3] after dQ (which also forms D), g_ev[4] after dK/dV
-        if ((e = hipEventSynchronize(g_ev[4])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    if (ps.bwd_seen) {
+        // backward events: ev[2] start, ev[3] after dQ (which also forms D), ev[4] after dK/dV
+        if ((e = hipEventSynchronize(ps.ev[4])) != hipSuccess) return hip_fail(e, "hipEventSynchronize");
         ms[1] = 0.0f;
-        if ((e = hipEventElapsedTime(&ms[3], g_ev[2], g_ev[3])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
-        if ((e = hipEventElapsedTime(&ms[2], g_ev[3], g_ev[4])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        if ((e = hipEventElapsedTime(&ms[3], ps.ev[2], ps.ev[3])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        if ((e = hipEventElapsedTime(&ms[2], ps.ev[3], ps.ev[4])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
     }
     return SKRULL_OK;
 }

@@ -24,6 +24,7 @@
 
 #include "common.h"
 #include "mfma.h"
+#include "queue.h"
 #include "tiles.h"
 
 namespace {
@@ -44,6 +45,9 @@ struct BwdParams {
     // ([head_split][total_k][Hkv][D] fp32) for dkv_reduce_kernel; 1 = no split
     int32_t head_split, total_k;
     float *dk_part, *dv_part;
+    WgTrace *trace_dq, *trace_dkv;  // null, or one record per work item (measurement aid)
+    WorkQueue *queue_dq, *queue_dkv;  // work queues of the persistent launches (workspace), zeroed before use
+    int32_t n_work_dq, n_work_dkv;    // work items: what a plain grid would have as workgroups
 };
 
 // ---------------------------------------------------------------------------
@@ -94,7 +98,7 @@ __device__ __forceinline__ uint32_t ds_mul_pack(float t0, float t1, float g0, fl
 // which is why the K ring has one slot more than the V ring.  Steps at the start, the
 // end and the causal diagonal of a wave's range take a plain path with guards.
 template <int D, int NWQ>
-__global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
+__device__ __forceinline__ void dq_work(const BwdParams &prm, const int bid)
 {
     constexpr bool SMALL = NWQ == NWQ_SMALL;
     constexpr int KSL = SMALL ? 3 : 5, VSL = SMALL ? 2 : 4;  // ring slots
@@ -113,8 +117,8 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     const int n = lane & 31, h = lane >> 5;
     // an item of more rows than the workgroup covers is split over `subs` workgroups
     const int subs = (prm.BM + 32 * NWQ - 1) / (32 * NWQ);
-    const int item_id = blockIdx.x / (prm.Hq * subs), sub = (blockIdx.x / prm.Hq) % subs;
-    const int hl = blockIdx.x % prm.Hq;
+    const int item_id = bid / (prm.Hq * subs), sub = (bid / prm.Hq) % subs;
+    const int hl = bid % prm.Hq;
     const int g = prm.Hq / prm.Hkv;
     const int c = hl % prm.Hkv;
     const int head = c * g + hl / prm.Hkv;
@@ -133,6 +137,7 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
     const int qrow0 = it.z + sub * 32 * NWQ;
     const int rows = min(32 * NWQ, min(prm.BM, ql - it.y * prm.BM) - sub * 32 * NWQ);
     if (rows <= 0) return;  // the item ends before this part (the whole workgroup leaves)
+    const uint64_t trace_t0 = trace_begin(prm.trace_dq);
     const int p0 = qb + row0;  // global position of the item's first query
     const int n_tiles = (p0 + rows + KT - 1) / KT;
     const float cs = prm.scale_log2;
@@ -389,6 +394,15 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
         if (oi < rows)
             store_rows_bf16<TT>(prm.dq + ((size_t)(qrow0 + oi) * prm.Hq + head) * D, acc, prm.scale, oh);
     }
+    trace_end(prm.trace_dq, trace_t0, bid);
+}
+
+template <int D, int NWQ>
+__global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
+{
+    __shared__ int work_slot;
+    work_loop(prm.queue_dq, prm.n_work_dq, &work_slot,
+              [&](int w) __attribute__((always_inline)) { dq_work<D, NWQ>(prm, w); });
 }
 
 // ---------------------------------------------------------------------------
@@ -457,7 +471,7 @@ __device__ __forceinline__ void ds_quad(uint32_t p01, uint32_t p23, const float 
 constexpr int PAIRS_8W = 4, PAIRS_12W = 6;
 
 template <int D, int PAIRS>
-__global__ __launch_bounds__(128 * PAIRS, PAIRS == PAIRS_12W ? 3 : 2) void dkv_kernel(const BwdParams prm)
+__device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
 {
     constexpr int NWP = 2 * PAIRS;   // wavefronts: PAIRS S waves, then PAIRS dP waves
     constexpr int SUB = 32 * PAIRS;  // key rows per workgroup
@@ -474,10 +488,10 @@ __global__ __launch_bounds__(128 * PAIRS, PAIRS == PAIRS_12W ? 3 : 2) void dkv_k
     // blockIdx -> (item, SUB-key pass of the item, KV head); an item of more key rows
     // than SUB is several workgroups
     const int passes = (prm.BN + SUB - 1) / SUB;
-    const int sub = blockIdx.x % passes;
+    const int sub = bid % passes;
     const int hs = prm.head_split;
-    const int hp = (blockIdx.x / passes) % hs;  // which share of the group's query heads
-    const int c = (blockIdx.x / passes / hs) % prm.Hkv, item_id = blockIdx.x / passes / hs / prm.Hkv;
+    const int hp = (bid / passes) % hs;  // which share of the group's query heads
+    const int c = (bid / passes / hs) % prm.Hkv, item_id = bid / passes / hs / prm.Hkv;
     const int g_all = prm.Hq / prm.Hkv;
     const int head_lo = (hp * g_all) / hs;
     const int g = ((hp + 1) * g_all) / hs - head_lo;  // >= 1 since head_split <= g_all
@@ -495,6 +509,7 @@ __global__ __launch_bounds__(128 * PAIRS, PAIRS == PAIRS_12W ? 3 : 2) void dkv_k
     const float cs = prm.scale_log2;
 
     if (sub * SUB >= item_rows) return;  // (whole workgroup) this item has no second pass
+    const uint64_t trace_t0 = trace_begin(prm.trace_dkv);
     const int kv0 = it.y * prm.BN + sub * SUB;  // first key position of the pass
     const int krows = min(SUB, kvl - kv0);
     const int wj0 = kv0 + 32 * pw;              // this pair's first key position
@@ -856,6 +871,15 @@ __global__ __launch_bounds__(128 * PAIRS, PAIRS == PAIRS_12W ? 3 : 2) void dkv_k
             store_rows_f32<TT>((role == 0 ? prm.dv_part : prm.dk_part) + part + off, acc, h);
         }
     }
+    trace_end(prm.trace_dkv, trace_t0, bid);
+}
+
+template <int D, int PAIRS>
+__global__ __launch_bounds__(128 * PAIRS, PAIRS == PAIRS_12W ? 3 : 2) void dkv_kernel(const BwdParams prm)
+{
+    __shared__ int work_slot;
+    work_loop(prm.queue_dkv, prm.n_work_dkv, &work_slot,
+              [&](int w) __attribute__((always_inline)) { dkv_work<D, PAIRS>(prm, w); });
 }
 
 // Sum of the head-split partial gradients, rounded once: out = bf16(mul * sum_p part[p]).
@@ -875,38 +899,39 @@ __global__ __launch_bounds__(256) void dkv_reduce_kernel(const float *__restrict
     ((uint2 *)out)[i] = w;
 }
 
+// true when the dQ kernel runs in its 4-wavefront shape (it fits the LDS twice only at head_dim 64)
+bool small_dq_shape(const skrull_attn_plan_t *p) { return p->d == 64 && p->wg_query_rows == 32 * NWQ_SMALL; }
+int dkv_pairs(const skrull_attn_plan_t *p) { return (p->d == 64 && p->BN == 32 * PAIRS_12W) ? PAIRS_12W : PAIRS_8W; }
+
 template <int D>
 hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream_t st, hipEvent_t *ev)
 {
     // dQ first: it also leaves -D and LSE*log2(e) of every (head, row) in the workspace,
     // which dK/dV reads.  Events: ev[0] start, ev[1] after dQ, ev[2] after dK/dV.
     if (ev) (void)hipEventRecord(ev[0], st);
-    const int gq = p->n_fwd * p->Hq;
+    queue_reset_kernel<<<1, 64, 0, st>>>(prm.queue_dq, 2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     bool small_dq = false;
     if constexpr (D == 64) {  // the small shape fits the LDS twice only at head_dim 64
-        if (p->wg_query_rows == 32 * NWQ_SMALL) {
-            const int subs = (p->BM + 32 * NWQ_SMALL - 1) / (32 * NWQ_SMALL);
-            dq_kernel<D, NWQ_SMALL><<<gq * subs, 64 * NWQ_SMALL, 0, st>>>(prm);
+        if (small_dq_shape(p)) {
+            e = launch_persistent<dq_kernel<D, NWQ_SMALL>>(64 * NWQ_SMALL, prm.n_work_dq, prm, st);
             small_dq = true;
         }
     }
-    if (!small_dq) dq_kernel<D, NWQ_LARGE><<<gq, 64 * NWQ_LARGE, 0, st>>>(prm);
-    hipError_t e = hipGetLastError();
+    if (!small_dq) e = launch_persistent<dq_kernel<D, NWQ_LARGE>>(64 * NWQ_LARGE, prm.n_work_dq, prm, st);
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
     {
-        const int pairs = (D == 64 && p->BN == 32 * PAIRS_12W) ? PAIRS_12W : PAIRS_8W;
-        const int gk = p->n_dkv * p->Hkv * p->head_split * ((p->BN + 32 * pairs - 1) / (32 * pairs));
         bool done = false;
         if constexpr (D == 64) {
-            if (pairs == PAIRS_12W) {
-                dkv_kernel<D, PAIRS_12W><<<gk, 128 * PAIRS_12W, 0, st>>>(prm);
+            if (dkv_pairs(p) == PAIRS_12W) {
+                e = launch_persistent<dkv_kernel<D, PAIRS_12W>>(128 * PAIRS_12W, prm.n_work_dkv, prm, st);
                 done = true;
             }
         }
-        if (!done) dkv_kernel<D, PAIRS_8W><<<gk, 128 * PAIRS_8W, 0, st>>>(prm);
+        if (!done) e = launch_persistent<dkv_kernel<D, PAIRS_8W>>(128 * PAIRS_8W, prm.n_work_dkv, prm, st);
     }
-    e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p->head_split > 1) {
         const int64_t n4 = (int64_t)p->total_k * p->Hkv * D / 4;
@@ -922,11 +947,25 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream
 
 }  // namespace
 
+int grid_dq(const skrull_attn_plan_t *p)
+{
+    const int subs = small_dq_shape(p) ? (p->BM + 32 * NWQ_SMALL - 1) / (32 * NWQ_SMALL) : 1;
+    return p->n_fwd * p->Hq * subs;
+}
+
+int grid_dkv(const skrull_attn_plan_t *p)
+{
+    const int pairs = dkv_pairs(p);
+    return p->n_dkv * p->Hkv * p->head_split * ((p->BN + 32 * pairs - 1) / (32 * pairs));
+}
+
 hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,
                       const void *o, const float *lse, const void *d_o, void *dq, void *dk,
-                      void *dv, float *delta, hipStream_t st, hipEvent_t *ev)
+                      void *dv, float *delta, hipStream_t st, hipEvent_t *ev, WgTrace *trace)
 {
     BwdParams prm;
+    prm.trace_dq = trace;
+    prm.trace_dkv = trace ? trace + grid_dq(p) : nullptr;
     prm.q = (const uint16_t *)q; prm.k = (const uint16_t *)k; prm.v = (const uint16_t *)v;
     prm.d_o = (const uint16_t *)d_o; prm.o = (const uint16_t *)o; prm.lse = lse; prm.delta = delta;
     prm.lse2 = delta + (size_t)p->Hq * p->total_q;
@@ -937,10 +976,14 @@ hipError_t launch_bwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM; prm.BN = p->BN;
     prm.scale = p->scale; prm.scale_log2 = p->scale * kLog2e;
     prm.head_split = p->head_split; prm.total_k = p->total_k;
+    prm.n_work_dq = grid_dq(p);
+    prm.n_work_dkv = grid_dkv(p);
     {
-        // workspace: -D | LSE*log2e | (256-byte aligned) dK partials | dV partials
+        // workspace: -D | LSE*log2e | (256-byte aligned) two work queues in 256 bytes | dK partials | dV partials
         const size_t rows = (((size_t)p->Hq * p->total_q * 8) + 255) & ~(size_t)255;
-        prm.dk_part = (float *)((char *)delta + rows);
+        prm.queue_dq = (WorkQueue *)((char *)delta + rows);
+        prm.queue_dkv = prm.queue_dq + 1;
+        prm.dk_part = (float *)((char *)delta + rows + 256);
         prm.dv_part = prm.dk_part + (size_t)p->head_split * p->total_k * p->Hkv * p->d;
     }
     if (p->d == 128) return launch_d<128>(p, prm, st, ev);

@@ -32,6 +32,7 @@
 
 #include "common.h"
 #include "mfma.h"
+#include "queue.h"
 #include "tiles.h"
 
 namespace {
@@ -47,6 +48,9 @@ struct FwdParams {
     int32_t Hq, Hkv, total_q, BM;
     int32_t variant;  // 0: 4 wavefronts, 128 rows per workgroup; 1: 8 wavefronts, 256 rows
     float scale_log2;  // softmax_scale * log2(e)
+    WgTrace *trace;    // null, or one record per work item (measurement aid)
+    WorkQueue *queue;  // work queue of the persistent launch, zeroed before use
+    int32_t n_work;    // work items: what a plain grid would have as workgroups
 };
 
 // Two shapes of the one kernel.  Large: 8 wavefronts = 256 query rows per workgroup and
@@ -111,7 +115,7 @@ __device__ __forceinline__ uint32_t softmax_sum_pack(float t0, float t1, float &
 }
 
 template <int D, int NW, int NSLOT>
-__global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
+__device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
 {
     static_assert(NSLOT == 2 || NSLOT == 4, "ring logic below covers two and four slots");
     constexpr int SM = NSLOT - 1;  // slot of tile t: t & SM
@@ -131,13 +135,13 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int n = lane & 31, h = lane >> 5;
 
-    // blockIdx -> (item, head).  Consecutive blocks go to consecutive XCDs; the
+    // work index -> (item, head).  Consecutive blocks go to consecutive XCDs; the
     // heads of one KV group are Hkv blocks apart so that they share an XCD (and
     // its L2 copy of the K/V tiles) whenever Hkv divides 8 or is a multiple of it.
     // an item of more rows than the workgroup covers is split over `subs` workgroups
     const int subs = (prm.BM + 32 * NW - 1) / (32 * NW);
-    const int item_id = blockIdx.x / (prm.Hq * subs), sub = (blockIdx.x / prm.Hq) % subs;
-    const int hl = blockIdx.x % prm.Hq;
+    const int item_id = bid / (prm.Hq * subs), sub = (bid / prm.Hq) % subs;
+    const int hl = bid % prm.Hq;
     const int g = prm.Hq / prm.Hkv;
     const int c = hl % prm.Hkv;
     const int head = c * g + hl / prm.Hkv;
@@ -159,6 +163,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
     const int qrow0 = it.z + sub * 32 * NW;
     const int rows = min(32 * NW, item_rows - sub * 32 * NW);
     if (rows <= 0) return;  // the item ends before this part (the whole workgroup leaves)
+    const uint64_t trace_t0 = trace_begin(prm.trace);
     const int p0 = qb + row0;  // global position of the pass's first query
     const int n_tiles = (p0 + rows + KT - 1) / KT;
 
@@ -421,24 +426,38 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
                     (m_run + __log2f(l_tot)) * 0.6931471805599453f;
         }
     }
+    trace_end(prm.trace, trace_t0, bid);
+}
+
+template <int D, int NW, int NSLOT>
+__global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
+{
+    __shared__ int work_slot;
+    work_loop(prm.queue, prm.n_work, &work_slot,
+              [&](int w) __attribute__((always_inline)) { fwd_work<D, NW, NSLOT>(prm, w); });
 }
 
 template <int D>
-hipError_t launch_one(const FwdParams &prm, int grid, hipStream_t st)
+hipError_t launch_one(const FwdParams &prm, hipStream_t st)
 {
-    if (prm.variant == 0) {
-        const int subs = (prm.BM + 32 * NW_SMALL - 1) / (32 * NW_SMALL);
-        fwd_kernel<D, NW_SMALL, NSLOT_SMALL><<<grid * subs, 64 * NW_SMALL, 0, st>>>(prm);
-    } else {
-        fwd_kernel<D, NW_LARGE, NSLOT_LARGE><<<grid, 64 * NW_LARGE, 0, st>>>(prm);
-    }
-    return hipGetLastError();
+    queue_reset_kernel<<<1, 64, 0, st>>>(prm.queue, 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (prm.variant == 0)
+        return launch_persistent<fwd_kernel<D, NW_SMALL, NSLOT_SMALL>>(64 * NW_SMALL, prm.n_work, prm, st);
+    return launch_persistent<fwd_kernel<D, NW_LARGE, NSLOT_LARGE>>(64 * NW_LARGE, prm.n_work, prm, st);
 }
 
 }  // namespace
 
+int grid_fwd(const skrull_attn_plan_t *p)
+{
+    const int subs = p->wg_query_rows == 32 * NW_SMALL ? (p->BM + 32 * NW_SMALL - 1) / (32 * NW_SMALL) : 1;
+    return p->n_fwd * p->Hq * subs;
+}
+
 hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k, const void *v,
-                      void *o, float *lse, hipStream_t st)
+                      void *o, float *lse, hipStream_t st, WgTrace *trace)
 {
     FwdParams prm;
     prm.q = (const uint16_t *)q; prm.k = (const uint16_t *)k; prm.v = (const uint16_t *)v;
@@ -447,9 +466,13 @@ hipError_t launch_fwd(const skrull_attn_plan_t *p, const void *q, const void *k,
     prm.cu_k = p->cu_k; prm.q_begin = p->q_begin; prm.q_len = p->q_len; prm.kv_len = p->kv_len;
     prm.Hq = p->Hq; prm.Hkv = p->Hkv; prm.total_q = p->total_q; prm.BM = p->BM;
     prm.scale_log2 = p->scale * 1.4426950408889634f;
-    const int grid = p->n_fwd * p->Hq;
+    prm.trace = trace;
     prm.variant = p->wg_query_rows == 32 * NW_SMALL ? 0 : 1;
-    if (p->d == 128) return launch_one<128>(prm, grid, st);
-    if (p->d == 64) return launch_one<64>(prm, grid, st);
+    prm.n_work = grid_fwd(p);
+    // One of the plan's queue slots per call, taken in turn, so that forward calls of one plan
+    // that overlap on different streams do not share a queue.
+    prm.queue = p->fwd_queues + (__atomic_fetch_add(&const_cast<skrull_attn_plan_t *>(p)->fwd_calls, 1u, __ATOMIC_RELAXED) % SKRULL_FWD_QUEUE_SLOTS);
+    if (p->d == 128) return launch_one<128>(prm, st);
+    if (p->d == 64) return launch_one<64>(prm, st);
     return hipErrorInvalidValue;
 }

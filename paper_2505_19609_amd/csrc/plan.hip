@@ -53,13 +53,57 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
     int32_t max_k_rows, int32_t *__restrict__ q_begin, int32_t *__restrict__ q_len,
     int32_t *__restrict__ kv_len, int32_t *__restrict__ cu_q, int32_t *__restrict__ cu_k,
     int32_t *__restrict__ shares_kv, int32_t *__restrict__ fwd_off, int32_t *__restrict__ dkv_off,
-    int32_t cap_fwd, int32_t cap_dkv, PlanTotals *__restrict__ totals)
+    int32_t cap_fwd, int32_t cap_dkv, int32_t bn_alt, int32_t kv_heads, int32_t compute_units,
+    PlanTotals *__restrict__ totals)
 {
     __shared__ int64_t lds[kScanThreads];
     __shared__ int32_t first_bad;
     const int t = threadIdx.x;
     if (t == 0) first_bad = 0x7fffffff;
     __syncthreads();
+    // Choice between BN and a larger dK/dV block bn_alt (0 = no choice to make): the larger
+    // one is taken when, with blocks of BN key rows, the costliest work item exceeds an even
+    // share of the whole list over the compute units (cost_max > cost_sum * Hkv / CUs), the
+    // same ratio that decides the head split.  The costs are those of the dK/dV items that
+    // plan_emit_kernel would write for BN.
+    if (bn_alt != 0) {
+        int64_t c_sum = 0, c_max = 0;
+        for (int32_t k = t; k < K; k += kScanThreads) {
+            const int64_t s = S[k], n = N[k], r = R[k], z = Z[k];
+            const int64_t chunks = n * (z ? 2 : 1);
+            if (s < 1 || n < 1 || r < 0 || r >= n || (z != 0 && z != 1) || chunks > s) continue;
+            const int64_t idx[2] = {r, 2 * n - 1 - r};
+            const int nseg = (int)z + 1;
+            int64_t qb[2], qe[2];
+            for (int part = 0; part < nseg; ++part) {
+                qb[part] = (idx[part] * s) / chunks;
+                qe[part] = ((idx[part] + 1) * s) / chunks;
+            }
+            for (int64_t j0 = 0; j0 < qe[nseg - 1]; j0 += BN) {
+                int64_t cost = 0;
+                for (int part = 0; part < nseg; ++part) {
+                    if (j0 >= qe[part]) continue;
+                    const int64_t i0 = j0 > qb[part] ? j0 - qb[part] : 0;
+                    cost += ceil_div64(qe[part] - qb[part], BM) - i0 / BM;
+                }
+                c_sum += cost;
+                c_max = cost > c_max ? cost : c_max;
+            }
+        }
+        int64_t tot;
+        block_exclusive_scan(c_sum, lds, &tot);
+        c_sum = tot;
+        // maximum over the block through the same LDS array
+        lds[t] = c_max;
+        __syncthreads();
+        for (int off = kScanThreads / 2; off > 0; off >>= 1) {
+            if (t < off && lds[t + off] > lds[t]) lds[t] = lds[t + off];
+            __syncthreads();
+        }
+        c_max = lds[0];
+        __syncthreads();
+        if (c_max * compute_units > c_sum * kv_heads) BN = bn_alt;
+    }
     int64_t base_s = 0, base_q = 0, base_k = 0, base_f = 0, base_d = 0, pairs = 0;
     for (int32_t k0 = 0; k0 < K; k0 += kScanThreads) {
         const int32_t k = k0 + t;
@@ -134,7 +178,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
         totals->dkv_cost_max = 0;
         totals->cap_fwd = cap_fwd;
         totals->cap_dkv = cap_dkv;
-        totals->pad = 0;
+        totals->block_n = BN;
     }
 }
 
@@ -150,7 +194,7 @@ __device__ inline int32_t owner_of(const int32_t *off, int32_t K, int32_t item)
 }
 
 __global__ __launch_bounds__(256) void plan_emit_kernel(
-    int32_t K, int32_t BM, int32_t BN, const int32_t *__restrict__ q_begin,
+    int32_t K, int32_t BM, const int32_t *__restrict__ q_begin,
     const int32_t *__restrict__ q_len, const int32_t *__restrict__ kv_len,
     const int32_t *__restrict__ cu_q, const int32_t *__restrict__ shares_kv,
     const int32_t *__restrict__ fwd_off,
@@ -161,6 +205,7 @@ __global__ __launch_bounds__(256) void plan_emit_kernel(
     // ranges kernel's (clamped: a count past the limit is rejected by the host afterwards)
     const int32_t n_fwd = (int32_t)min((long long)totals->n_fwd, (long long)totals->cap_fwd);
     const int32_t n_dkv = (int32_t)min((long long)totals->n_dkv, (long long)totals->cap_dkv);
+    const int32_t BN = totals->block_n;  // the ranges kernel's choice where the caller left it open
     const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n_fwd) {
         const int32_t k = owner_of(fwd_off, K, t);
@@ -226,11 +271,13 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
                               int32_t max_q_rows, int32_t max_k_rows, int32_t *q_begin,
                               int32_t *q_len, int32_t *kv_len, int32_t *cu_q, int32_t *cu_k,
                               int32_t *shares_kv, int32_t *fwd_off, int32_t *dkv_off,
-                              int32_t cap_fwd, int32_t cap_dkv, PlanTotals *totals, hipStream_t st)
+                              int32_t cap_fwd, int32_t cap_dkv, int32_t bn_alt, int32_t kv_heads,
+                              int32_t compute_units, PlanTotals *totals, hipStream_t st)
 {
     plan_ranges_kernel<<<1, kScanThreads, 0, st>>>(S, N, r, cut, K, BM, BN, max_q_rows, max_k_rows,
                                                    q_begin, q_len, kv_len, cu_q, cu_k, shares_kv,
-                                                   fwd_off, dkv_off, cap_fwd, cap_dkv, totals);
+                                                   fwd_off, dkv_off, cap_fwd, cap_dkv, bn_alt, kv_heads,
+                                                   compute_units, totals);
     return hipGetLastError();
 }
 
@@ -243,7 +290,7 @@ hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off
     // counts from `totals` on the device, so no round trip to the host is needed in between
     const int32_t n = cap_fwd > cap_dkv ? cap_fwd : cap_dkv;
     plan_emit_kernel<<<(n + 255) / 256, 256, 0, st>>>(
-        p->NS, p->BM, p->BN, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off,
+        p->NS, p->BM, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off,
         (int4 *)scratch_fwd, (int4 *)scratch_dkv, totals);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -83,6 +83,12 @@ def test_null_arguments(B):
     assert L.skrull_attn_plan_export(None, 0, None, 0) == B.SKRULL_EINVAL
     assert L.skrull_attn_fwd(None, None, None, None, None, None, None) == B.SKRULL_EINVAL
     assert L.skrull_attn_bwd(*([None] * 11), 0, None) == B.SKRULL_EINVAL
+    assert L.skrull_attn_bwd_static(*([None] * 11)) == B.SKRULL_EINVAL
+    assert L.skrull_attn_trace_layout(None, None, None) == B.SKRULL_EINVAL
+    assert L.skrull_attn_trace(None, 0) == B.SKRULL_OK            # "off" needs no device
+    assert L.skrull_attn_profile_read(None) == B.SKRULL_EINVAL
+    import ctypes as C
+    assert L.skrull_attn_profile_read((C.c_float * 4)()) == B.SKRULL_EINVAL   # this thread never enabled it
     L.skrull_attn_plan_destroy(None)
 
 
