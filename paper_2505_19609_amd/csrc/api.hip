@@ -50,7 +50,7 @@ struct TraceState {
 };
 thread_local TraceState g_trace;
 
-constexpr int32_t kMaxItems = 1 << 20;  // rank-counting sort is quadratic in the item count
+constexpr int32_t kMaxItems = 1 << 20;  // per list (lists above 16,384 items are radix sorted)
 
 // Workspace of skrull_attn_bwd_static, the backward entry point for callers that cannot
 // allocate: one array per GPU that the library runs on, held until the process ends.
@@ -186,7 +186,11 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     // totals | unsorted items
     const int64_t kin = align4(K), kpad = align4(n_seg + 1);
     const int64_t totals_ints = align4((int64_t)((sizeof(PlanTotals) + 3) / 4));
-    const int64_t tmp_ints = 4 * kin + 2 * kpad + totals_ints + 4 * (cap_fwd + cap_dkv);
+    // no work item costs more than this many blocks (64 rows is the smallest block; a two-chunk
+    // cut adds the query blocks of both chunks)
+    const int32_t cost_bound = 2 * (longest_seq / 64 + 2);
+    const int64_t radix_ints = plan_radix_ints((int32_t)cap_fwd, (int32_t)cap_dkv, cost_bound);
+    const int64_t tmp_ints = 4 * kin + 2 * kpad + totals_ints + 4 * (cap_fwd + cap_dkv) + radix_ints;
     const int64_t desc_ints = 6 * kpad;
     const int64_t queue_ints = SKRULL_FWD_QUEUE_SLOTS * 16;  // 64-byte work queues of the forward launches
     int32_t *fwd_off = nullptr, *dkv_off = nullptr, *scratch = nullptr;
@@ -229,7 +233,7 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
                                fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, bn_alt, p->num_kv_heads,
                                compute_units, totals_d, st));
     HIP_TRY(launch_plan_items(plan, fwd_off, dkv_off, (int32_t)cap_fwd, (int32_t)cap_dkv, scratch,
-                              scratch + 4 * cap_fwd, totals_d, st));
+                              scratch + 4 * cap_fwd, scratch + 4 * (cap_fwd + cap_dkv), cost_bound, totals_d, st));
     HIP_TRY(hipMemcpyAsync(&totals, totals_d, sizeof totals, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (totals.bad_entry != 0 || totals.n_seg != plan->NS || totals.total_q > INT32_MAX ||

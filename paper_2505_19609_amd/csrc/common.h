@@ -79,10 +79,14 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
                               int32_t *shares_kv, int32_t *fwd_off, int32_t *dkv_off,
                               int32_t cap_fwd, int32_t cap_dkv, int32_t bn_alt, int32_t kv_heads,
                               int32_t compute_units, PlanTotals *totals, hipStream_t st);
+// `cost_bound`: no work item costs more (host's bound from the longest sequence); lists whose
+// upper bound of items exceeds the rank sort's limit are radix sorted and need
+// plan_radix_ints(...) ints of scratch at `radix_hist`
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
                              const int32_t *dkv_off, int32_t cap_fwd, int32_t cap_dkv,
-                             int32_t *scratch_fwd, int32_t *scratch_dkv, PlanTotals *totals,
-                             hipStream_t st);
+                             int32_t *scratch_fwd, int32_t *scratch_dkv, int32_t *radix_hist,
+                             int32_t cost_bound, PlanTotals *totals, hipStream_t st);
+int64_t plan_radix_ints(int32_t cap_fwd, int32_t cap_dkv, int32_t cost_bound);
 
 // fwd.hip / bwd.hip
 // `trace` (may be null): room for one WgTrace per workgroup of every kernel launched, in

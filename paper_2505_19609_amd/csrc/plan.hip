@@ -264,6 +264,85 @@ __global__ __launch_bounds__(256) void plan_sort_kernel(const int4 *__restrict__
     if (a < n) out[rank] = me;
 }
 
+// ---------------------------------------------------------------------------
+// Long lists: stable least-significant-digit radix sort on key = key_max - cost
+// (ascending key = descending cost), 8 bits per pass, 1024 consecutive items per
+// block.  Three kernels per pass: per-block digit histogram; exclusive scan of the
+// (digit, block) table in digit-major order; scatter, in which an item's offset is
+// its digit's start + the items of that digit in earlier blocks + those before it
+// in its own block (which keeps equal keys in their order: the sort is stable).
+// ---------------------------------------------------------------------------
+constexpr int kRadixBlock = 1024;
+
+__device__ inline int32_t list_length(const PlanTotals *totals, int which)
+{
+    return which == 0 ? (int32_t)min((long long)totals->n_fwd, (long long)totals->cap_fwd)
+                      : (int32_t)min((long long)totals->n_dkv, (long long)totals->cap_dkv);
+}
+
+__global__ __launch_bounds__(256) void radix_hist_kernel(const int4 *__restrict__ in,
+                                                         const PlanTotals *__restrict__ totals, int which,
+                                                         int32_t key_max, int shift, int32_t nb,
+                                                         int32_t *__restrict__ hist)
+{
+    __shared__ int32_t h[256];
+    const int32_t n = list_length(totals, which);
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int32_t base = blockIdx.x * kRadixBlock;
+    for (int32_t i = threadIdx.x; i < kRadixBlock; i += 256)
+        if (base + i < n) atomicAdd(&h[((key_max - in[base + i].w) >> shift) & 255], 1);
+    __syncthreads();
+    hist[threadIdx.x * nb + blockIdx.x] = h[threadIdx.x];
+}
+
+// one block; thread d scans the counts of digit d over the blocks, then the digits are scanned
+__global__ __launch_bounds__(256) void radix_scan_kernel(int32_t *__restrict__ hist, int32_t nb)
+{
+    __shared__ int64_t lds[kScanThreads];
+    const int d = threadIdx.x;
+    int32_t run = 0;
+    for (int32_t b = 0; b < nb; ++b) {
+        const int32_t c = hist[d * nb + b];
+        hist[d * nb + b] = run;
+        run += c;
+    }
+    int64_t tot;
+    const int32_t start = (int32_t)block_exclusive_scan(run, lds, &tot);
+    for (int32_t b = 0; b < nb; ++b) hist[d * nb + b] += start;
+}
+
+__global__ __launch_bounds__(256) void radix_scatter_kernel(const int4 *__restrict__ in,
+                                                            const PlanTotals *__restrict__ totals, int which,
+                                                            int32_t key_max, int shift, int32_t nb,
+                                                            const int32_t *__restrict__ hist,
+                                                            int4 *__restrict__ out)
+{
+    __shared__ unsigned char dig[kRadixBlock];
+    const int32_t n = list_length(totals, which);
+    const int32_t base = blockIdx.x * kRadixBlock;
+    const int32_t cnt = min(kRadixBlock, n - base);
+    if (cnt <= 0) return;
+    // thread t owns the consecutive items 4t .. 4t+3 of the block
+    int4 mine[4];
+    for (int e = 0; e < 4; ++e) {
+        const int32_t i = 4 * threadIdx.x + e;
+        if (i < cnt) {
+            mine[e] = in[base + i];
+            dig[i] = (unsigned char)(((key_max - mine[e].w) >> shift) & 255);
+        }
+    }
+    __syncthreads();
+    for (int e = 0; e < 4; ++e) {
+        const int32_t i = 4 * threadIdx.x + e;
+        if (i >= cnt) break;
+        const unsigned char d = dig[i];
+        int32_t before = 0;  // items of the same digit earlier in this block
+        for (int32_t j = 0; j < i; ++j) before += dig[j] == d;
+        out[hist[(int32_t)d * nb + blockIdx.x] + before] = mine[e];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t *r,
@@ -281,24 +360,70 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
     return hipGetLastError();
 }
 
+// Above this many items (the host's upper bound) a list is sorted by radix passes instead of
+// by rank counting, which is quadratic: 16,384 items take it 0.27e9 comparisons.
+constexpr int32_t kRankSortMax = 16384;
+
+int plan_radix_passes(int32_t cap, int32_t cost_bound)
+{
+    if (cap <= kRankSortMax) return 0;
+    int bits = 1;
+    while (bits < 31 && (1 << bits) <= cost_bound) ++bits;
+    return (bits + 7) / 8;
+}
+
+int64_t plan_radix_ints(int32_t cap_fwd, int32_t cap_dkv, int32_t cost_bound)
+{
+    int64_t n = 0;
+    if (plan_radix_passes(cap_fwd, cost_bound)) n += 256 * (int64_t)((cap_fwd + kRadixBlock - 1) / kRadixBlock);
+    if (plan_radix_passes(cap_dkv, cost_bound)) n += 256 * (int64_t)((cap_dkv + kRadixBlock - 1) / kRadixBlock);
+    return n;
+}
+
+// Sort one list.  `a` holds the emitted items when the number of passes is odd (or zero), `b`
+// when it is even, so that the last pass (or the rank sort) always writes the plan's array `b`.
+static hipError_t sort_list(int which, int32_t cap, int32_t cost_bound, int4 *a, int4 *b, int32_t *hist,
+                            PlanTotals *totals, hipStream_t st)
+{
+    const int passes = plan_radix_passes(cap, cost_bound);
+    if (passes == 0) {
+        plan_sort_kernel<<<(cap + 255) / 256, 256, 0, st>>>(a, totals, which, b);
+        return hipGetLastError();
+    }
+    int key_bits = 8 * passes;
+    const int32_t key_max = key_bits >= 31 ? INT32_MAX : (1 << key_bits) - 1;  // >= any cost
+    const int32_t nb = (cap + kRadixBlock - 1) / kRadixBlock;
+    int4 *src = (passes & 1) ? a : b, *dst = (passes & 1) ? b : a;
+    for (int pass = 0; pass < passes; ++pass) {
+        radix_hist_kernel<<<nb, 256, 0, st>>>(src, totals, which, key_max, 8 * pass, nb, hist);
+        radix_scan_kernel<<<1, 256, 0, st>>>(hist, nb);
+        radix_scatter_kernel<<<nb, 256, 0, st>>>(src, totals, which, key_max, 8 * pass, nb, hist, dst);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        int4 *t = src; src = dst; dst = t;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_plan_items(const skrull_attn_plan_t *p, const int32_t *fwd_off,
                              const int32_t *dkv_off, int32_t cap_fwd, int32_t cap_dkv,
-                             int32_t *scratch_fwd, int32_t *scratch_dkv, PlanTotals *totals,
-                             hipStream_t st)
+                             int32_t *scratch_fwd, int32_t *scratch_dkv, int32_t *radix_hist,
+                             int32_t cost_bound, PlanTotals *totals, hipStream_t st)
 {
     // grids are sized by the host's upper bounds of the item counts; the kernels take the
     // counts from `totals` on the device, so no round trip to the host is needed in between
     const int32_t n = cap_fwd > cap_dkv ? cap_fwd : cap_dkv;
+    // the emit kernel writes each list where its sort starts from
+    const bool fwd_even = plan_radix_passes(cap_fwd, cost_bound) != 0 && plan_radix_passes(cap_fwd, cost_bound) % 2 == 0;
+    const bool dkv_even = plan_radix_passes(cap_dkv, cost_bound) != 0 && plan_radix_passes(cap_dkv, cost_bound) % 2 == 0;
     plan_emit_kernel<<<(n + 255) / 256, 256, 0, st>>>(
         p->NS, p->BM, p->q_begin, p->q_len, p->kv_len, p->cu_q, p->shares_kv, fwd_off, dkv_off,
-        (int4 *)scratch_fwd, (int4 *)scratch_dkv, totals);
+        (int4 *)(fwd_even ? p->fwd_items : scratch_fwd), (int4 *)(dkv_even ? p->dkv_items : scratch_dkv), totals);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    plan_sort_kernel<<<(cap_fwd + 255) / 256, 256, 0, st>>>((const int4 *)scratch_fwd, totals, 0,
-                                                            (int4 *)p->fwd_items);
-    e = hipGetLastError();
+    int32_t *hist_dkv = radix_hist;
+    if (plan_radix_passes(cap_fwd, cost_bound)) hist_dkv += 256 * (int64_t)((cap_fwd + kRadixBlock - 1) / kRadixBlock);
+    e = sort_list(0, cap_fwd, cost_bound, (int4 *)scratch_fwd, (int4 *)p->fwd_items, radix_hist, totals, st);
     if (e != hipSuccess) return e;
-    plan_sort_kernel<<<(cap_dkv + 255) / 256, 256, 0, st>>>((const int4 *)scratch_dkv, totals, 1,
-                                                            (int4 *)p->dkv_items);
-    return hipGetLastError();
+    return sort_list(1, cap_dkv, cost_bound, (int4 *)scratch_dkv, (int4 *)p->dkv_items, hist_dkv, totals, st);
 }

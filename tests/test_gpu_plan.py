@@ -97,3 +97,21 @@ def test_plan_rejects_oversized_total():
     with pytest.raises(B.SkrullError) as e:
         B.skrull_attn_plan([2 ** 30, 2 ** 30, 2 ** 30], [1] * 3, [0] * 3, 8, 8, 128, 0.1)
     assert e.value.code == B.SKRULL_EINVAL
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("longest,passes", [(250, 1), (10_000, 2), (4_200_000, 3)])
+def test_plan_long_lists_are_radix_sorted(oracle, longest, passes):
+    """More than 16,384 work items per list: the plan sorts by stable radix passes (one, two or
+    three 8-bit digits, depending on the largest possible cost) instead of by rank counting;
+    the layout stays exactly the oracle's."""
+    rng = np.random.Generator(np.random.PCG64(70 + passes))
+    S = rng.integers(1, 250, size=18_000).tolist()
+    if longest > 250:
+        S.insert(7, longest)
+    N = [int(min(s, n)) for s, n in zip(S, rng.integers(1, 4, size=len(S)))]
+    R = [int(rng.integers(0, n)) for n in N]
+    if longest > 250:
+        N[7], R[7] = 1, 0
+    assert 2 * (longest // 64 + 2) >= 256 ** (passes - 1) and 2 * (longest // 64 + 2) < 256 ** passes
+    _check(oracle, S, N, R, 1, 1, 64, 64, 64)
