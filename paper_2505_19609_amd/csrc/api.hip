@@ -50,7 +50,7 @@ struct TraceState {
 };
 thread_local TraceState g_trace;
 
-constexpr int32_t kMaxItems = 1 << 20;  // per list (lists above 16,384 items are radix sorted)
+constexpr int32_t kMaxItems = 1 << 20;  // per list (lists above 2,048 items are radix sorted)
 
 // Workspace of skrull_attn_bwd_static, the backward entry point for callers that cannot
 // allocate: one array per GPU that the library runs on, held until the process ends.

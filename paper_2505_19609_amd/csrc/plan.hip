@@ -22,21 +22,27 @@ constexpr int kScanThreads = 256;
 
 // Block-wide exclusive scan of one int64 per thread; returns the exclusive
 // prefix and writes the block total to *total (same value in every thread).
+// Inside a wavefront the scan runs on lane shuffles; the four wavefronts' totals
+// meet in LDS (two barriers per scan).
 __device__ inline int64_t block_exclusive_scan(int64_t v, int64_t *lds, int64_t *total)
 {
-    const int t = threadIdx.x;
-    lds[t] = v;
-    __syncthreads();
-    for (int off = 1; off < kScanThreads; off <<= 1) {
-        int64_t add = (t >= off) ? lds[t - off] : 0;
-        __syncthreads();
-        lds[t] += add;
-        __syncthreads();
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int64_t incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
     }
-    const int64_t incl = lds[t];
-    *total = lds[kScanThreads - 1];
+    if (lane == 63) lds[wave] = incl;
     __syncthreads();
-    return incl - v;
+    int64_t before = 0, all = 0;
+    for (int w = 0; w < kScanThreads / 64; ++w) {
+        const int64_t x = lds[w];
+        if (w < wave) before += x;
+        all += x;
+    }
+    *total = all;
+    __syncthreads();  // lds may be reused by the next scan
+    return before + incl - v;
 }
 
 __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -361,8 +367,9 @@ hipError_t launch_plan_ranges(const int32_t *S, const int32_t *N, const int32_t 
 }
 
 // Above this many items (the host's upper bound) a list is sorted by radix passes instead of
-// by rank counting, which is quadratic: 16,384 items take it 0.27e9 comparisons.
-constexpr int32_t kRankSortMax = 16384;
+// by rank counting, which is quadratic (measured: 0.25 ms for 5,000 items, 3 ms for 16,000; the
+// radix passes take 0.05 ms there).
+constexpr int32_t kRankSortMax = 2048;
 
 int plan_radix_passes(int32_t cap, int32_t cost_bound)
 {

@@ -102,7 +102,7 @@ def test_plan_rejects_oversized_total():
 @pytest.mark.timeout(300)
 @pytest.mark.parametrize("longest,passes", [(250, 1), (10_000, 2), (4_200_000, 3)])
 def test_plan_long_lists_are_radix_sorted(oracle, longest, passes):
-    """More than 16,384 work items per list: the plan sorts by stable radix passes (one, two or
+    """More than 2,048 work items per list (here 18,000 and more): the plan sorts by stable radix passes (one, two or
     three 8-bit digits, depending on the largest possible cost) instead of by rank counting;
     the layout stays exactly the oracle's."""
     rng = np.random.Generator(np.random.PCG64(70 + passes))
