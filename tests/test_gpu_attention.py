@@ -504,9 +504,9 @@ def test_config3_llama8b_sampled(oracle, capsys):
 
 @pytest.mark.timeout(600)
 def test_config4_shard7_sampled(oracle, capsys):
-    """Every query row of this slice sees 114,688 to 131,072 keys: the sampled rows of the slice
-    are compared on 8 seeded heads each, and the key columns come from the last 3,700 keys."""
-    _sampled(oracle, W.config(4), ROWS, COLS, seed=404, capsys=capsys, heads_per_row=8, few_heads_from=65536)
+    """Every query row of this slice sees 114,688 to 131,072 keys; its key columns come from the
+    last 7,700 keys of the prefix (what 4e9 row-key-head triples of oracle forward afford)."""
+    _sampled(oracle, W.config(4), ROWS, COLS, seed=404, capsys=capsys, slice_group_cap=4.0e9)
 
 
 @pytest.mark.timeout(600)
@@ -527,13 +527,23 @@ def test_config4_quarter_twin(oracle, capsys, index, cut):
     _sampled(oracle, w, ROWS, COLS, seed=407 + cut, capsys=capsys)
 
 
+@pytest.mark.timeout(600)
+def test_config4_two_chunk_rank2_sampled(oracle, capsys):
+    """Config 4's micro-batch with the 131,072-token sequence cut the balanced way (rank 2 of
+    8 holds chunks 2 and 13 of 16, 8,192 rows each, on a prefix of 114,688 keys): key columns
+    from the tail of the prefix that the cap affords, which spans the late chunk's boundary."""
+    w = W.config(4, shard_index=2)
+    w.shard_cut = [1] + [0] * (len(w.seq_len) - 1)
+    w.name += "_two_chunks"
+    _sampled(oracle, w, ROWS, COLS, seed=406, capsys=capsys, slice_group_cap=3.0e9)
+
+
 @pytest.mark.timeout(800)
 def test_config5_qwen7b_sampled(oracle, capsys):
     """The 38,365-token local sequence gets the whole forward of one KV group (7 query heads,
     5.2e9) and key columns over its whole prefix; the slice 3 of 4 of the 65,536-token sequence
-    a tail of its prefix, and 8 seeded heads per sampled row."""
-    _sampled(oracle, W.config(5), ROWS, COLS, seed=505, capsys=capsys, heads_per_row=8, few_heads_from=65536,
-             group_cap=5.5e9, slice_group_cap=1.0e9)
+    a tail of its prefix."""
+    _sampled(oracle, W.config(5), ROWS, COLS, seed=505, capsys=capsys, group_cap=5.5e9, slice_group_cap=2.0e9)
 
 
 @pytest.mark.timeout(400)
