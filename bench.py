@@ -203,6 +203,13 @@ def main():
                 "kernel_ms": {"fwd": round(float(kms[0]), 4), "dkv": round(float(kms[2]), 4),
                               "dq": round(float(kms[3]), 4)},
                 "kernel_tflops": {n.split("_")[0]: round(f / (t * 1e-3) / 1e12, 1) for n, (t, f) in kernels.items()},
+                # what the kernels execute on unmasked pairs: the dQ kernel recomputes S and dP (6 instead of 2
+                # flops per pair, head and head dim), the other two execute what they are credited with
+                "kernel_executed_tflops": {"fwd": round(4 * unit / (kms[0] * 1e-3) / 1e12, 1),
+                                           "dkv": round(8 * unit / (kms[2] * 1e-3) / 1e12, 1),
+                                           "dq": round(6 * unit / (kms[3] * 1e-3) / 1e12, 1),
+                                           "step": round(18 * unit / (ev_step * 1e-3) / 1e12, 1),
+                                           "step_frac_of_mfma_only_measured": round(18 * unit / (ev_step * 1e-3) / 1e12 / ceiling, 4)},
                 "hbm": {"algorithmic_bytes_per_step": int(alg_bytes),
                         "algorithmic_gbps": round(alg_bytes / (ev_step * 1e-3) / 1e9, 1),
                         "measured_bytes_per_step": int(sum(traffic.values())) if have_traffic else None,
