@@ -45,14 +45,37 @@ def cpu_baseline(w, np):
     vals = W.make_values(sub, desc["total_q"], desc["total_k"])
     f = {n: W.bf16_bits_to_f32(a) for n, a in vals.items()}
     t0 = time.perf_counter()
-    oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
-    oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
+    O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
+    dQ, dK, dV, _ = oracle.attention_bwd(f["q"], f["k"], f["v"], f["do"], desc, w.softmax_scale)
     dt = time.perf_counter() - t0
     useful = 14 * oracle.attended_pairs(desc) * w.head_dim * w.num_q_heads
-    return {"value": useful / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(dt, 3),
-            "sample": f"{len(S)} short sequences of the micro-batch ({sum(S)} tokens, "
-                      f"{oracle.attended_pairs(desc)} pairs), all {w.num_q_heads} query heads, fp64 fwd+bwd"}
+    out = {"value": useful / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+           "kind": "oracle", "seconds": round(dt, 3),
+           "sample": f"{len(S)} short sequences of the micro-batch ({sum(S)} tokens, "
+                     f"{oracle.attended_pairs(desc)} pairs), all {w.num_q_heads} query heads, fp64 fwd+bwd"}
+    # the library on the same sample, outside every timed region: largest deviation from the oracle
+    # per output, absolute and in spacings of bf16 at the reference value
+    import torch
+    from paper_2505_19609_amd import binding as B
+    plan = B.skrull_attn_plan(S, [1] * len(S), [0] * len(S), w.num_q_heads, w.num_kv_heads, w.head_dim,
+                              w.softmax_scale)
+    dev = {n: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) for n, a in vals.items()}
+    o, dq = torch.empty_like(dev["q"]), torch.empty_like(dev["q"])
+    dk, dv = torch.empty_like(dev["k"]), torch.empty_like(dev["k"])
+    lse = torch.empty((w.num_q_heads, plan.total_q), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(int(plan.bwd_workspace_bytes), 16), dtype=torch.uint8, device="cuda")
+    B.skrull_attn_fwd(plan, dev["q"], dev["k"], dev["v"], o, lse)
+    B.skrull_attn_bwd(plan, dev["q"], dev["k"], dev["v"], o, lse, dev["do"], dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    plan.destroy()
+    par = {}
+    for name, got, ref in (("O", o, O), ("LSE", lse, LSE), ("dQ", dq, dQ), ("dK", dk, dK), ("dV", dv, dV)):
+        err = np.abs(got.float().cpu().numpy() - ref)
+        i = np.unravel_index(np.argmax(err), err.shape)
+        spacing = 2.0 ** (np.floor(np.log2(max(abs(ref[i]), 2.0 ** -126))) - 7)
+        par[name] = {"max_abs": float(f"{err[i]:.3g}"), "in_bf16_spacings": round(float(err[i] / spacing), 2)}
+    out["gpu_vs_oracle_on_sample"] = par
+    return out
 
 
 def measured_traffic(workload, kernel):

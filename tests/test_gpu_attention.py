@@ -505,7 +505,7 @@ def test_config3_llama8b_sampled(oracle, capsys):
 @pytest.mark.timeout(600)
 def test_config4_shard7_sampled(oracle, capsys):
     """Every query row of this slice sees 114,688 to 131,072 keys; its key columns come from the
-    last 7,700 keys of the prefix (what 4e9 row-key-head triples of oracle forward afford)."""
+    last 7,865 keys of the prefix (what 4e9 row-key-head triples of oracle forward afford)."""
     _sampled(oracle, W.config(4), ROWS, COLS, seed=404, capsys=capsys, slice_group_cap=4.0e9)
 
 
