@@ -776,11 +776,14 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
             f32x16 dpn;
             bf16x8 fr[4], ft[4];
             uint32_t w[4][4];
-            const uint4 p0 = *(const uint4 *)(pp + 0 * 1024 + lane * 16);
-            const uint4 p1 = *(const uint4 *)(pp + 1 * 1024 + lane * 16);
+            // what the first MFMA waits for is asked for first (when the barrier opens all eight
+            // waves queue their reads at once): -D, the start of its accumulator, and dO
+            dpn = neg_d(0);
 #pragma unroll
             for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 0, x);
-            dpn = neg_d(0);
+            SB();
+            const uint4 p0 = *(const uint4 *)(pp + 0 * 1024 + lane * 16);
+            const uint4 p1 = *(const uint4 *)(pp + 1 * 1024 + lane * 16);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 dpn = mfma32(fr[ks % 4], bf[ks], dpn);
@@ -806,8 +809,12 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
             }
             const bf16x8 db2 = as_bf16x8(make_uint4(w[2][0], w[2][1], w[2][2], w[2][3]));
             const bf16x8 db3 = as_bf16x8(make_uint4(w[3][0], w[3][1], w[3][2], w[3][3]));
+            // dS of the previous tile is complete: its dP - D registers take the start of this
+            // tile's second block (-D) now, eight MFMAs before the products that need it
+            dp[1] = neg_d(1);
 #pragma unroll
             for (int x = 0; x < 3; ++x) fr[x] = fa.rows(tdo, 1, x);
+            SB();
 #pragma unroll
             for (int m = 2 * TT; m < 4 * TT; ++m) {
                 acc[m % TT] = mfma32(ft[m % 4], m < 3 * TT ? db2 : db3, acc[m % TT]);
@@ -816,7 +823,6 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
                 SB();
             }
             dp[0] = dpn;
-            dp[1] = neg_d(1);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 dp[1] = mfma32(fr[ks % 4], bf[ks], dp[1]);
