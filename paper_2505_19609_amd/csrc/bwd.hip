@@ -909,38 +909,29 @@ __global__ __launch_bounds__(256) void dkv_reduce_kernel(const float *__restrict
 bool small_dq_shape(const skrull_attn_plan_t *p) { return p->d == 64 && p->wg_query_rows == 32 * NWQ_SMALL; }
 int dkv_pairs(const skrull_attn_plan_t *p) { return (p->d == 64 && p->BN == 32 * PAIRS_12W) ? PAIRS_12W : PAIRS_8W; }
 
-template <int D>
-hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream_t st, hipEvent_t *ev)
+template <auto KernelQ, auto KernelKV>
+hipError_t launch_pair(const skrull_attn_plan_t *p, BwdParams prm, int threads_q, int threads_kv, hipStream_t st,
+                       hipEvent_t *ev)
 {
     // dQ first: it also leaves -D and LSE*log2(e) of every (head, row) in the workspace,
     // which dK/dV reads.  Events: ev[0] start, ev[1] after dQ, ev[2] after dK/dV.
     if (ev) (void)hipEventRecord(ev[0], st);
-    queue_reset_kernel<<<1, 64, 0, st>>>(prm.queue_dq, 2);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    bool small_dq = false;
-    if constexpr (D == 64) {  // the small shape fits the LDS twice only at head_dim 64
-        if (small_dq_shape(p)) {
-            e = launch_persistent<dq_kernel<D, NWQ_SMALL>>(64 * NWQ_SMALL, prm.n_work_dq, prm, st);
-            small_dq = true;
-        }
+    const bool queued_q = wants_queue<KernelQ>(threads_q, prm.n_work_dq);
+    const bool queued_kv = wants_queue<KernelKV>(threads_kv, prm.n_work_dkv);
+    if (queued_q || queued_kv) {
+        queue_reset_kernel<<<1, 64, 0, st>>>(prm.queue_dq, 2);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    if (!small_dq) e = launch_persistent<dq_kernel<D, NWQ_LARGE>>(64 * NWQ_LARGE, prm.n_work_dq, prm, st);
+    if (!queued_q) prm.queue_dq = nullptr;
+    if (!queued_kv) prm.queue_dkv = nullptr;
+    hipError_t e = launch_work<KernelQ>(threads_q, prm.n_work_dq, queued_q, prm, st);
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    {
-        bool done = false;
-        if constexpr (D == 64) {
-            if (dkv_pairs(p) == PAIRS_12W) {
-                e = launch_persistent<dkv_kernel<D, PAIRS_12W>>(128 * PAIRS_12W, prm.n_work_dkv, prm, st);
-                done = true;
-            }
-        }
-        if (!done) e = launch_persistent<dkv_kernel<D, PAIRS_8W>>(128 * PAIRS_8W, prm.n_work_dkv, prm, st);
-    }
+    e = launch_work<KernelKV>(threads_kv, prm.n_work_dkv, queued_kv, prm, st);
     if (e != hipSuccess) return e;
     if (p->head_split > 1) {
-        const int64_t n4 = (int64_t)p->total_k * p->Hkv * D / 4;
+        const int64_t n4 = (int64_t)p->total_k * p->Hkv * p->d / 4;
         const unsigned blocks = (unsigned)((n4 + 255) / 256);
         dkv_reduce_kernel<<<blocks, 256, 0, st>>>(prm.dk_part, p->head_split, n4, prm.scale, prm.dk);
         dkv_reduce_kernel<<<blocks, 256, 0, st>>>(prm.dv_part, p->head_split, n4, 1.0f, prm.dv);
@@ -949,6 +940,21 @@ hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream
     }
     if (ev) (void)hipEventRecord(ev[2], st);
     return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_d(const skrull_attn_plan_t *p, const BwdParams &prm, hipStream_t st, hipEvent_t *ev)
+{
+    if constexpr (D == 64) {  // the small dQ shape fits the LDS twice, and dK/dV has its 12-wavefront shape, only here
+        const bool small_q = small_dq_shape(p), wide_kv = dkv_pairs(p) == PAIRS_12W;
+        if (small_q && wide_kv)
+            return launch_pair<dq_kernel<D, NWQ_SMALL>, dkv_kernel<D, PAIRS_12W>>(p, prm, 64 * NWQ_SMALL, 128 * PAIRS_12W, st, ev);
+        if (small_q)
+            return launch_pair<dq_kernel<D, NWQ_SMALL>, dkv_kernel<D, PAIRS_8W>>(p, prm, 64 * NWQ_SMALL, 128 * PAIRS_8W, st, ev);
+        if (wide_kv)
+            return launch_pair<dq_kernel<D, NWQ_LARGE>, dkv_kernel<D, PAIRS_12W>>(p, prm, 64 * NWQ_LARGE, 128 * PAIRS_12W, st, ev);
+    }
+    return launch_pair<dq_kernel<D, NWQ_LARGE>, dkv_kernel<D, PAIRS_8W>>(p, prm, 64 * NWQ_LARGE, 128 * PAIRS_8W, st, ev);
 }
 
 }  // namespace

@@ -437,15 +437,25 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_kernel(const FwdParams prm)
               [&](int w) __attribute__((always_inline)) { fwd_work<D, NW, NSLOT>(prm, w); });
 }
 
+template <auto Kernel>
+hipError_t launch_shape(FwdParams prm, int threads, hipStream_t st)
+{
+    const bool queued = wants_queue<Kernel>(threads, prm.n_work);
+    if (queued) {
+        queue_reset_kernel<<<1, 64, 0, st>>>(prm.queue, 1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else {
+        prm.queue = nullptr;
+    }
+    return launch_work<Kernel>(threads, prm.n_work, queued, prm, st);
+}
+
 template <int D>
 hipError_t launch_one(const FwdParams &prm, hipStream_t st)
 {
-    queue_reset_kernel<<<1, 64, 0, st>>>(prm.queue, 1);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (prm.variant == 0)
-        return launch_persistent<fwd_kernel<D, NW_SMALL, NSLOT_SMALL>>(64 * NW_SMALL, prm.n_work, prm, st);
-    return launch_persistent<fwd_kernel<D, NW_LARGE, NSLOT_LARGE>>(64 * NW_LARGE, prm.n_work, prm, st);
+    if (prm.variant == 0) return launch_shape<fwd_kernel<D, NW_SMALL, NSLOT_SMALL>>(prm, 64 * NW_SMALL, st);
+    return launch_shape<fwd_kernel<D, NW_LARGE, NSLOT_LARGE>>(prm, 64 * NW_LARGE, st);
 }
 
 }  // namespace

@@ -93,14 +93,30 @@ static int resident_workgroups(K kernel, int threads)
     return cus * per_cu;
 }
 
-// Persistent launch: as many workgroups as fit the chip at once, at most one per work item;
-// each takes work items from the queue until none is left.
-template <auto Kernel, typename P>
-static hipError_t launch_persistent(int threads, int n_work, const P &prm, hipStream_t st)
+// Workgroups of a kernel (a template argument) that the chip holds at once; queried once.
+template <auto Kernel>
+static int resident_of(int threads)
 {
-    static const int resident = resident_workgroups(Kernel, threads);  // once per kernel (a template argument)
-    int grid = n_work;
-    if (resident > 0 && grid > resident) grid = resident;
+    static const int resident = resident_workgroups(Kernel, threads);
+    return resident;
+}
+
+// A launch needs its queue only when there are more work items than the chip holds workgroups at
+// once; otherwise one workgroup per item, all resident together, is the whole schedule.
+template <auto Kernel>
+static bool wants_queue(int threads, int n_work)
+{
+    const int resident = resident_of<Kernel>(threads);
+    return resident > 0 && n_work > resident;
+}
+
+// Persistent launch when `queued` (as many workgroups as fit the chip at once, each taking work
+// items from the queue in `prm` until none is left), else a plain grid of one workgroup per item
+// (`prm` then carries no queue).
+template <auto Kernel, typename P>
+static hipError_t launch_work(int threads, int n_work, bool queued, const P &prm, hipStream_t st)
+{
+    const int grid = queued ? resident_of<Kernel>(threads) : n_work;
     Kernel<<<grid, threads, 0, st>>>(prm);
     return hipGetLastError();
 }
