@@ -189,8 +189,9 @@ int skrull_attn_plan_export(const skrull_attn_plan_t *plan, int which, void *dst
  * empty and then the largest remaining item of the fullest other list (the dies of one chip
  * differ in speed by several percent, which a fixed deal of workgroups to dies cannot even
  * out).  Results do not depend on which workgroup took which item.
- * Only enqueues on `hip_stream` (a small kernel that clears the queue, then the attention
- * kernel); never synchronises.
+ * Only enqueues on `hip_stream` (the attention kernel and, when there are more work items than
+ * the chip holds workgroups at once, a small kernel that clears the queue before it); never
+ * synchronises.
  * SKRULL_EINVAL on a null or misaligned pointer, or when the current device is
  * not the one the plan was made on.
  */

@@ -15,6 +15,8 @@ SOURCES = ["api.hip", "plan.hip", "fwd.hip", "bwd.hip", "probe.hip", "dacp.cpp",
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
+# further compiler flags for experiments (space separated), e.g. SKRULL_EXTRA_FLAGS="-mllvm -align-loops=64"
+FLAGS += os.environ.get("SKRULL_EXTRA_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:
