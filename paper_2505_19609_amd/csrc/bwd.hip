@@ -170,36 +170,50 @@ __device__ __forceinline__ void dq_work(const BwdParams &prm, const int bid)
             ld.load(rv, ring_v + (uint32_t)((t + 3) & 3) * TB, (t + 3) * KT, wave);
         }
     };
-    // start-up: the tiles of the first period(s) and, with them, the fetch group of period 0
-    // (its slots are empty), so that a short sequence pays the fetch latency once
+    // start-up: the tiles of the first period(s).  The fetch group of period 0 follows after the
+    // barrier below, because until then its slots stage this item's rows of Q, dO and O.
     ld.load(rk, ring_k, 0, wave);
     ld.load(rv, ring_v, 0, wave);
-    if (SMALL) {
-        if (1 < n_tiles) fetch(0);
-    } else {
+    if (!SMALL) {
         ld.load(rk, ring_k + TB, KT, wave);
         ld.load(rv, ring_v + TB, KT, wave);
-        if (2 < n_tiles) fetch(0);
     }
+    // this wave's staging region: half a ring slot that holds no tile yet (large shape: K slots
+    // 2-4 for waves 0-5 and V slots 2-3 for waves 6-7; small shape: K slots 1-2)
+    typedef WaveStage<D> Stage;
+    static_assert(2 * Stage::BYTES == TB, "two staging regions per ring slot");
+    const uint32_t stage = SMALL ? ring_k + TB + (uint32_t)wave * Stage::BYTES
+                                 : (wave < 6 ? ring_k + 2 * TB + (uint32_t)wave * Stage::BYTES
+                                             : ring_v + 2 * TB + (uint32_t)(wave - 6) * Stage::BYTES);
 
     // B operands held for the whole item: this lane's query row of Q and dO
     bf16x8 qf[KS], dof[KS];
     float lse2, nd;
     {
+        Stage st;
+        st.init(lane);
+        const uint32_t pitch = (uint32_t)prm.Hq * D * 2;
+        const size_t hoff = ((size_t)qrow0 * prm.Hq + head) * D;
+        u32x4 vq[Stage::N], vg[Stage::N], vo[Stage::N];
+        st.load(vq, prm.q + hoff, pitch, wrow0, rows);
+        st.load(vg, prm.d_o + hoff, pitch, wrow0, rows);
+        st.load(vo, prm.o + hoff, pitch, wrow0, rows);
         const int my_row = qrow0 + min(my_i, rows - 1);  // packed row, clamped for loads
-        const size_t off = ((size_t)my_row * prm.Hq + head) * D + 8 * h;
+        lse2 = prm.lse[(size_t)head * prm.total_q + my_row] * kLog2e;
+        st.put(stage, vq);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qf[ks] = as_bf16x8(*(const uint4 *)(prm.q + off + 16 * ks));
-            dof[ks] = as_bf16x8(*(const uint4 *)(prm.d_o + off + 16 * ks));
-        }
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = fa.rows_at(stage, ks);
+        st.put(stage, vg);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) dof[ks] = fa.rows_at(stage, ks);
+        st.put(stage, vo);
         // D = rowsum(dO * O) of this lane's row (each half of the wave holds half of the
-        // head dims) and LSE in the exp2 domain; the dK/dV kernel, launched after this one,
-        // reads both from the workspace (it takes -D as the start of its dP accumulator)
+        // head dims) and LSE in the exp2 domain; both are stored at the end of the item for the
+        // dK/dV kernel, launched after this one (it takes -D as the start of its dP accumulator)
         float dsum = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const uint4 ow = *(const uint4 *)(prm.o + off + 16 * ks);
+            const uint4 ow = __builtin_bit_cast(uint4, fa.rows_at(stage, ks));
             const uint4 gw = __builtin_bit_cast(uint4, dof[ks]);
             const uint32_t a[4] = {ow.x, ow.y, ow.z, ow.w}, b[4] = {gw.x, gw.y, gw.z, gw.w};
 #pragma unroll
@@ -209,17 +223,13 @@ __device__ __forceinline__ void dq_work(const BwdParams &prm, const int bid)
             }
         }
         nd = -add_other_half(dsum);
-        lse2 = prm.lse[(size_t)head * prm.total_q + my_row] * kLog2e;
-        if (h == 0 && my_i < rows) {
-            prm.delta[(size_t)head * prm.total_q + my_row] = nd;
-            prm.lse2[(size_t)head * prm.total_q + my_row] = lse2;
-        }
     }
     // Everything issued so far has to land here: the compiler's own count of
     // outstanding loads must be zero before the loops, or the waits it places
     // for these fragments would also wait for the tile fetches in flight.
     wait_vmem();
     __syncthreads();
+    if ((SMALL ? 1 : 2) < n_tiles) fetch(0);  // the staging regions are free again
 
     f32x16 acc[TT];
     zero_acc(acc);
@@ -385,14 +395,21 @@ __device__ __forceinline__ void dq_work(const BwdParams &prm, const int bid)
 #pragma unroll 1
     for (; t <= n_tiles; ++t) plain_period(t);
 
+    __syncthreads();  // nobody reads a tile any more: the staging regions are free
     if (wave_active) {
         // derived after the loop from opaque copies, so that no part of the
-        // output address is kept in registers during the loop
+        // output addresses is kept in registers during the loop
         int li = lane;
         asm volatile("" : "+v"(li));
         const int on = li & 31, oh = li >> 5, oi = wrow0 + on;
-        if (oi < rows)
-            store_rows_bf16<TT>(prm.dq + ((size_t)(qrow0 + oi) * prm.Hq + head) * D, acc, prm.scale, oh);
+        Stage st;
+        st.init(li);
+        st.put_acc(stage, acc, prm.scale, on, oh);
+        st.store(stage, prm.dq + ((size_t)qrow0 * prm.Hq + head) * D, (uint32_t)prm.Hq * D * 2, wrow0, rows);
+        if (oh == 0 && oi < rows) {
+            prm.delta[(size_t)head * prm.total_q + qrow0 + oi] = nd;
+            prm.lse2[(size_t)head * prm.total_q + qrow0 + oi] = lse2;
+        }
     }
     trace_end(prm.trace_dq, trace_t0, bid);
 }
@@ -516,13 +533,23 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
     const bool wave_active = 32 * pw < krows;
     const int my_j = wj0 + n;                   // this lane's key position
 
+    // this wave's staging region: ring slots 1 and 2 hold no tile at the start and the end of a
+    // pass (eight regions); the waves beyond the eighth use the P exchange area
+    typedef WaveStage<D> Stage;
+    static_assert(8 * Stage::BYTES <= 2 * SLOT && (NWP - 8) * Stage::BYTES <= (int)sizeof(lds_p),
+                  "staging regions do not fit the idle part of the LDS");
+    const uint32_t stage = wave < 8 ? ring0 + SLOT + (uint32_t)wave * Stage::BYTES
+                                    : lds_addr(&lds_p[0][0][0][0]) + (uint32_t)(wave - 8) * Stage::BYTES;
     // B operand held for the whole pass: this lane's key row of K (role 0) or V (role 1).
     bf16x8 bf[KS];
     {
-        const uint16_t *src = role == 0 ? prm.k : prm.v;
-        const size_t off = ((size_t)(kbase + min(my_j, kvl - 1)) * prm.Hkv + c) * D + 8 * h;
+        Stage st;
+        st.init(lane);
+        u32x4 vk[Stage::N];
+        st.load(vk, (role == 0 ? prm.k : prm.v) + ((size_t)kbase * prm.Hkv + c) * D, (uint32_t)prm.Hkv * D * 2, wj0, kvl);
+        st.put(stage, vk);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bf[ks] = as_bf16x8(*(const uint4 *)(src + off + 16 * ks));
+        for (int ks = 0; ks < KS; ++ks) bf[ks] = fa.rows_at(stage, ks);
     }
 
     // Query tiles that can see key kv0, numbered 0 .. n_qt-1 in position order: those of
@@ -867,12 +894,16 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
         round_begin(T);
         round_end();
     }
-    if (wave_active && my_j < kvl) {
-        const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
+    // (the last round ended with a barrier: nobody reads a tile or P any more)
+    if (wave_active) {
         if (hs == 1) {
-            if (role == 0) store_rows_bf16<TT>(prm.dv + off, acc, 1.0f, h);
-            else store_rows_bf16<TT>(prm.dk + off, acc, prm.scale, h);
-        } else {
+            Stage st;
+            st.init(lane);
+            st.put_acc(stage, acc, role == 0 ? 1.0f : prm.scale, n, h);
+            st.store(stage, (role == 0 ? prm.dv : prm.dk) + ((size_t)kbase * prm.Hkv + c) * D,
+                     (uint32_t)prm.Hkv * D * 2, wj0, kvl);
+        } else if (my_j < kvl) {
+            const size_t off = ((size_t)(kbase + my_j) * prm.Hkv + c) * D;
             const size_t part = (size_t)hp * prm.total_k * prm.Hkv * D;
             store_rows_f32<TT>((role == 0 ? prm.dv_part : prm.dk_part) + part + off, acc, h);
         }

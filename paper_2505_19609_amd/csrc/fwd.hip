@@ -328,28 +328,41 @@ __device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
         }
     };
 
-    // Start-up: the tiles of the first period and, with them, the fetch group of period 0
-    // (its slots are empty), so that a short sequence pays the fetch latency once.
+    // Start-up: the tiles of the first period.  The rest of period 0's fetch group follows after
+    // the barrier below, because until then its slots stage this item's rows of Q.
     ld.load(rk, ring_k, 0, wave);  // K tile 0
-    if (NSLOT == 4) {
-        ld.load(rk, ring_k + TB, KT, wave);  // K tile 1
-        ld.load(rv, ring_v, 0, wave);        // V tile 0
-        if (1 < n_tiles) fetch(0);
-    } else {
-        fetch(0);
-    }
-
+    if (NSLOT == 4) ld.load(rk, ring_k + TB, KT, wave);  // K tile 1
+    ld.load(rv, ring_v, 0, wave);  // V tile 0
+    // this wave's staging region: half a ring slot that holds no tile yet (four slots: K slots
+    // 2-3 for waves 0-3, V slots 1-2 for waves 4-7; two slots: K slot 1 for waves 0-1, V slot 1
+    // for waves 2-3)
+    typedef WaveStage<D> Stage;
+    static_assert(2 * Stage::BYTES == TB, "two staging regions per ring slot");
+    static_assert((NSLOT == 4 && NW == 8) || (NSLOT == 2 && NW == 4), "staging regions are laid out for these shapes");
+    const uint32_t stage = NSLOT == 4 ? (wave < 4 ? ring_k + 2 * TB + (uint32_t)wave * Stage::BYTES
+                                                  : ring_v + TB + (uint32_t)(wave - 4) * Stage::BYTES)
+                                      : (wave < 2 ? ring_k + TB + (uint32_t)wave * Stage::BYTES
+                                                  : ring_v + TB + (uint32_t)(wave - 2) * Stage::BYTES);
     {
-        const uint16_t *qp =
-            prm.q + ((size_t)(qrow0 + min(my_i, rows - 1)) * prm.Hq + head) * D + 8 * h;
+        Stage st;
+        st.init(lane);
+        u32x4 vq[Stage::N];
+        st.load(vq, prm.q + ((size_t)qrow0 * prm.Hq + head) * D, (uint32_t)prm.Hq * D * 2, wrow0, rows);
+        st.put(stage, vq);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = as_bf16x8(*(const uint4 *)(qp + 16 * ks));
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = fa.rows_at(stage, ks);
     }
     // Everything issued so far has to land here: the compiler's own count of
     // outstanding loads must be zero before the loops, or the waits it places
     // for these fragments would also wait for the tile fetches in flight.
     wait_vmem();
     __syncthreads();
+    // the staging regions are free again: what is left of period 0's fetch group
+    if (NSLOT == 4) {
+        if (1 < n_tiles) fetch(0);
+    } else {
+        ld.load(rk, ring_k + TB, KT, wave);  // K tile 1
+    }
 
     f32x16 sx, sy;         // S of the current / next half tile, ping-pong
     bf16x8 px[2], py[2];   // P of the previous / current half tile, ping-pong
@@ -411,6 +424,7 @@ __device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
 #pragma unroll 1
     for (; t <= n_tiles; ++t) plain_period(t);
 
+    __syncthreads();  // nobody reads a tile any more: the staging regions are free
     if (wave_active) {
         const float l_tot = sum_halves(l_run);
         const float inv = 1.0f / l_tot;
@@ -419,12 +433,12 @@ __device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
         int li = lane;
         asm volatile("" : "+v"(li));
         const int on = li & 31, oh = li >> 5, oi = wrow0 + on;
-        if (oi < rows) {
-            store_rows_bf16<TT>(prm.o + ((size_t)(qrow0 + oi) * prm.Hq + head) * D, oacc, inv, oh);
-            if (oh == 0)
-                prm.lse[(size_t)head * prm.total_q + qrow0 + oi] =
-                    (m_run + __log2f(l_tot)) * 0.6931471805599453f;
-        }
+        Stage st;
+        st.init(li);
+        st.put_acc(stage, oacc, inv, on, oh);
+        st.store(stage, prm.o + ((size_t)qrow0 * prm.Hq + head) * D, (uint32_t)prm.Hq * D * 2, wrow0, rows);
+        if (oh == 0 && oi < rows)
+            prm.lse[(size_t)head * prm.total_q + qrow0 + oi] = (m_run + __log2f(l_tot)) * 0.6931471805599453f;
     }
     trace_end(prm.trace, trace_t0, bid);
 }

@@ -70,6 +70,12 @@ struct FragAddr {
     {
         return *(const bf16x8 *)(t + rm + b * (32 * G::ROWB) + ks * 32);
     }
+    // the same fragment of the first 32 rows of a tile-shaped region given by its LDS address
+    __device__ __forceinline__ bf16x8 rows_at(uint32_t region, int ks) const
+    {
+        typedef bf16x8 __attribute__((address_space(3))) * lds_frag_t;
+        return *(lds_frag_t)(uintptr_t)(region + rm + ks * 32);
+    }
     __device__ __forceinline__ bf16x8 cols(const unsigned char *t, int tt, int kbg) const
     {
         typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
@@ -200,6 +206,85 @@ __device__ __forceinline__ void store_rows_f32(float *dst, const f32x16 (&acc)[T
             *(float4 *)(dst + 32 * tt + 8 * vb + 4 * h) =
                 make_float4(acc[tt][4 * vb + 0], acc[tt][4 * vb + 1], acc[tt][4 * vb + 2], acc[tt][4 * vb + 3]);
 }
+
+// ---------------------------------------------------------------------------
+// Per-wave staging of a 32-row block of one head of a [rows, H, D] matrix.
+//
+// A lane of a 32x32 MFMA owns one ROW of such a block (B operand: 16 bytes of it per
+// k-step; result: 8 bytes per four accumulator registers).  Loading or storing the block
+// straight from that layout touches 32 rows per instruction, 16 or 8 bytes of each: 64
+// separate cache requests per instruction, and the 8 to 24 such instructions per lane at
+// the start and end of a work item kept the address path busy for 3 to 14 us per item.
+// Here the wave moves the block in whole rows instead (64 lanes x 16 bytes = 4 rows at
+// D = 128, 8 rows at D = 64 per instruction) and turns it in a private LDS region laid out
+// like the first half of a tile (32 rows, same pitch and row permutation), so the operand
+// fragments come back through FragAddr::rows_at and results go in by quads.  LDS
+// instructions of one wave execute in order, so the region needs no barrier between its
+// write and read; the caller makes sure no other wave uses the same bytes as a tile
+// meanwhile.  Regions are given as 32-bit LDS addresses.
+// ---------------------------------------------------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x4 __attribute__((address_space(3))) * lds_u4_t;
+typedef u32x2 __attribute__((address_space(3))) * lds_u2_t;
+
+template <int D>
+struct WaveStage {
+    typedef TileGeom<D> G;
+    static constexpr int BYTES = 32 * G::ROWB;  // 8704 (D=128) / 4608 (D=64)
+    static constexpr int N = 32 * G::CH / 64;   // whole-row instructions per block: 8 / 4
+    static constexpr int RPI = 64 / G::CH;      // rows per instruction: 4 / 8
+    int r_in, c16;                              // this lane's row inside an instruction's rows; its byte column
+
+    __device__ __forceinline__ void init(int lane)
+    {
+        r_in = lane / G::CH;
+        c16 = (lane % G::CH) * 16;
+    }
+    // rows first .. first+31 of a matrix of `rows` >= 1 rows (row index clamped to the last one);
+    // `base` points at row 0, column 0 of the head
+    __device__ __forceinline__ void load(u32x4 (&v)[N], const uint16_t *base, uint32_t pitch_bytes, int first,
+                                         int rows) const
+    {
+        const unsigned char *b = (const unsigned char *)base + c16;
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            v[j] = *(const u32x4 *)(b + (size_t)min(first + j * RPI + r_in, rows - 1) * pitch_bytes);
+    }
+    __device__ __forceinline__ void put(uint32_t region, const u32x4 (&v)[N]) const
+    {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            *(lds_u4_t)(uintptr_t)(region + row_pos(j * RPI + r_in) * G::ROWB + c16) = v[j];
+    }
+    // 32 (d) x 32 (row) accumulator tiles of this lane's row n (half h), scaled, as bf16
+    template <int TT>
+    __device__ __forceinline__ void put_acc(uint32_t region, const f32x16 (&acc)[TT], float mul, int n, int h) const
+    {
+        const uint32_t a = region + row_pos(n) * G::ROWB + 8 * h;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) {
+                u32x2 w;
+                w.x = pack_bf16(acc[tt][4 * vb + 0] * mul, acc[tt][4 * vb + 1] * mul);
+                w.y = pack_bf16(acc[tt][4 * vb + 2] * mul, acc[tt][4 * vb + 3] * mul);
+                *(lds_u2_t)(uintptr_t)(a + 64 * tt + 16 * vb) = w;
+            }
+    }
+    // the staged block to rows first .. first+31 of the matrix (those below `rows`), whole rows per instruction
+    __device__ __forceinline__ void store(uint32_t region, uint16_t *base, uint32_t pitch_bytes, int first,
+                                          int rows) const
+    {
+        unsigned char *b = (unsigned char *)base + c16;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const u32x4 w = *(lds_u4_t)(uintptr_t)(region + row_pos(j * RPI + r_in) * G::ROWB + c16);
+            const int r = first + j * RPI + r_in;
+            if (r < rows) *(u32x4 *)(b + (size_t)r * pitch_bytes) = w;
+        }
+    }
+};
 
 // x + (x of the lane 32 away).  Written out with the operands copied first: given one
 // value for both operands, the swap builtin returns its first result twice.
