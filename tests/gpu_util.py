@@ -8,9 +8,33 @@ def to_dev(bits):
     return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
 
 
+GUARD = 2048        # elements of margin on each side of a guarded tensor (a multiple of 16 bytes)
+GUARD_VALUE = 12352.0  # exact in bf16 and fp32; no kernel output of the tests comes near it
+
+
+def guarded(shape, dtype, fill):
+    """A tensor of `shape` filled with `fill`, inside a larger buffer whose margins hold GUARD_VALUE
+    (uint8: 0xA5).  Returns (whole buffer, the tensor)."""
+    import torch
+    n = int(np.prod(shape))
+    mark = 0xA5 if dtype == torch.uint8 else GUARD_VALUE
+    buf = torch.full((n + 2 * GUARD,), mark, dtype=dtype, device="cuda")
+    view = buf[GUARD:GUARD + n]
+    view.fill_(fill)
+    return buf, view.view(shape)
+
+
+def margins_intact(buf):
+    import torch
+    mark = 0xA5 if buf.dtype == torch.uint8 else GUARD_VALUE
+    return bool((buf[:GUARD] == mark).all().item()) and bool((buf[-GUARD:] == mark).all().item())
+
+
 def run_library(w, block_m=0, block_n=0, vals=None, backward=True, keep_device=False, head_split=0,
-                wg_query_rows=0):
-    """Plan + forward (+ backward) of workload ``w`` on the current GPU."""
+                wg_query_rows=0, guard=False):
+    """Plan + forward (+ backward) of workload ``w`` on the current GPU.  With `guard` every
+    output and the workspace sit between margins that are checked afterwards: out["margins"]
+    names the tensors whose margins were written to (none, if every store stayed inside)."""
     import torch
     from paper_2505_19609_amd import binding as B
     from paper_2505_19609_amd import workloads as W
@@ -21,17 +45,27 @@ def run_library(w, block_m=0, block_n=0, vals=None, backward=True, keep_device=F
     if vals is None:
         vals = W.make_values(w, plan.total_q, plan.total_k)
     dev = {n: to_dev(a) for n, a in vals.items()}
-    o = torch.full_like(dev["q"], float("nan"))
-    lse = torch.full((w.num_q_heads, plan.total_q), float("nan"), dtype=torch.float32, device="cuda")
+    bufs = {}
+
+    def alloc(name, shape, dtype, fill=float("nan")):
+        if not guard:
+            return torch.full(shape, fill, dtype=dtype, device="cuda")
+        bufs[name], t = guarded(shape, dtype, fill)
+        return t
+
+    o = alloc("o", tuple(dev["q"].shape), torch.bfloat16)
+    lse = alloc("lse", (w.num_q_heads, plan.total_q), torch.float32)
     B.skrull_attn_fwd(plan, dev["q"], dev["k"], dev["v"], o, lse)
     out = {"plan": plan, "vals": vals}
     if backward:
-        dq = torch.full_like(dev["q"], float("nan"))
-        dk = torch.full_like(dev["k"], float("nan"))
-        dv = torch.full_like(dev["v"], float("nan"))
-        ws = torch.empty(max(int(plan.bwd_workspace_bytes), 16), dtype=torch.uint8, device="cuda")
+        dq = alloc("dq", tuple(dev["q"].shape), torch.bfloat16)
+        dk = alloc("dk", tuple(dev["k"].shape), torch.bfloat16)
+        dv = alloc("dv", tuple(dev["v"].shape), torch.bfloat16)
+        ws = alloc("workspace", (max(int(plan.bwd_workspace_bytes), 16),), torch.uint8, 0)
         B.skrull_attn_bwd(plan, dev["q"], dev["k"], dev["v"], o, lse, dev["do"], dq, dk, dv, ws)
     torch.cuda.synchronize()
+    if guard:
+        out["margins"] = [n for n, b in bufs.items() if not margins_intact(b)]
     res = {"o": o, "lse": lse}
     if backward:
         res.update(dq=dq, dk=dk, dv=dv)

@@ -104,6 +104,25 @@ EDGE = {
 
 
 @pytest.mark.parametrize("name", sorted(EDGE))
+@pytest.mark.parametrize("heads,d,wg,hs", [((4, 4), 64, 0, 0), ((6, 2), 128, 256, 3), ((8, 1), 128, 128, 0),
+                                           ((14, 2), 64, 256, 7)])
+def test_every_store_stays_inside_its_tensor(name, heads, d, wg, hs):
+    """Outputs and workspace sit between marked margins: a store of a row block that ran past the
+    end of a ragged micro-batch (or before its start) would change them.  Every element inside
+    is written (no NaN of the pre-fill is left) and the result equals the unguarded run's bits."""
+    S, N, R = EDGE[name]
+    w = W.Workload(f"guard_{name}", S, N, R, heads[0], heads[1], d, d ** -0.5, 77)
+    a = run_library(w, head_split=hs, wg_query_rows=wg, guard=True)
+    assert a["margins"] == [], a["margins"]
+    b = run_library(w, head_split=hs, wg_query_rows=wg)
+    for n in ("o", "lse", "dq", "dk", "dv"):
+        assert np.isfinite(a[n]).all(), n
+        assert np.array_equal(a[n], b[n]), n
+    a["plan"].destroy()
+    b["plan"].destroy()
+
+
+@pytest.mark.parametrize("name", sorted(EDGE))
 @pytest.mark.parametrize("heads,d", [((4, 4), 64), ((6, 2), 128), ((8, 1), 128), ((2, 1), 64)])
 def test_edge_cases(oracle, name, heads, d):
     S, N, R = EDGE[name]
