@@ -137,8 +137,11 @@ enum {
  * sequence of 8,192 tokens or more is present or the work list is short (the
  * dK/dV kernel then runs 12 wavefronts over 192 key rows); head_split above 1
  * when the longest dK/dV chain exceeds an even share of the work list;
- * wg_query_rows 128 at head_dim 64 and for micro-batches without sequences
- * above 8,192 tokens, else 256.  None of them changes a result beyond the
+ * wg_query_rows 128 when the micro-batch holds enough work for the smaller
+ * workgroups to pay (head_dim 64: at least 24 blocks of 256 query rows x heads
+ * per compute unit or 1.5e9 attended (query, key, head) triples; head_dim 128:
+ * at least 16 such blocks and no sequence above 8,192 tokens), else 256.  None
+ * of them changes a result beyond the
  * last bit of dK/dV (head_split changes the order of the sum over heads).
  *
  * p and the three arrays it points to are HOST memory, read before return.

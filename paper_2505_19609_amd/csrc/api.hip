@@ -256,15 +256,27 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
     // the compute units.  When the longest chain exceeds that share (few KV heads, one
     // long sequence in a small micro-batch) the heads of a group are shared out over
     // several workgroups until it no longer does, with a factor two of slack.
-    // Workgroup shape of the forward and dQ kernels.  Two 4-wavefront workgroups per
-    // compute unit hide each other's start-up, drain and barriers.  Forward: 8-21 % faster
-    // at head_dim 64 at every length measured (256 ... 65,536) and at head_dim 128 up to
-    // 4,096-token sequences, equal at 8,192, 1-2 % slower beyond, where the 8-wavefront
-    // workgroup's deeper tile ring and halved tile traffic win.  dQ: the small shape fits
-    // twice into the LDS only at head_dim 64; there it is 17 % (256 tokens) to 2 % (65,536)
-    // faster.
-    plan->wg_query_rows = p->wg_query_rows != 0 ? p->wg_query_rows
-                         : (p->head_dim == 64 || longest_seq <= 8192) ? 128 : 256;
+    // Workgroup shape of the forward and dQ kernels.  Several 4-wavefront workgroups per compute
+    // unit hide each other's start-up, drain and barriers, but they also stretch each other's
+    // work items (three share a unit and its oldest wave is served first), and a launch ends only
+    // when its last stretched item does; so the small shape pays once the launch holds enough
+    // work to bury that tail.  Measured on 8 to 64 query heads x 16,384 to 32,768 tokens x
+    // sequences of 256 to 32,768 tokens: at head_dim 64 the small shape wins (forward by 3-15 %,
+    // dQ by 1-6 %) when the micro-batch has at least 24 blocks of 256 query rows x heads per
+    // compute unit or at least 1.5e9 attended (query, key, head) triples, and loses by 2-90 %
+    // (forward) below that; at head_dim 128 (forward only: the small dQ shape does not fit the LDS
+    // twice) it wins by 1-8 % from 16 such blocks per compute unit on while no sequence exceeds
+    // 8,192 tokens, where the 8-wavefront workgroup's deeper tile ring and halved tile traffic
+    // take over.
+    if (p->wg_query_rows != 0) {
+        plan->wg_query_rows = p->wg_query_rows;
+    } else {
+        const double blocks_per_cu = (double)plan->Hq * (double)totals.total_q / (256.0 * (double)compute_units);
+        const double triples = (double)totals.pairs * (double)plan->Hq;
+        const bool small_shape = p->head_dim == 64 ? (blocks_per_cu >= 24.0 || triples >= 1.5e9)
+                                                   : (longest_seq <= 8192 && blocks_per_cu >= 16.0);
+        plan->wg_query_rows = small_shape ? 128 : 256;
+    }
     plan->head_split = p->head_split;
     if (plan->head_split == 0) {
         // Split only when the longest chain of the work list (its costliest item, all the

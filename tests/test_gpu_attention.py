@@ -752,15 +752,24 @@ def test_shapes_and_block_sizes_change_no_bit(d):
     base["plan"].destroy()
 
 
-def test_workgroup_shape_is_chosen_from_head_dim_and_length():
+def test_workgroup_shape_is_chosen_from_head_dim_and_amount_of_work():
+    """wg_query_rows left open: 128 once the micro-batch holds enough work for the smaller
+    workgroups to pay (head_dim 64: 24 blocks of 256 query rows x heads per compute unit, or 1.5e9
+    attended (query, key, head) triples; head_dim 128: 16 such blocks and no sequence above 8,192
+    tokens), else 256.  (256 compute units: 32 heads x 32,768 rows are 16 blocks per unit.)"""
     from paper_2505_19609_amd import binding as B
-    for S, d, want in (([8192, 100], 128, 128), ([8193, 100], 128, 256), ([65536], 64, 128),
-                       ([131072], 128, 256), ([300], 128, 128)):
+    for S, heads, d, want in (([8192] * 4, (32, 8), 128, 128), ([8193] + [8192] * 3, (32, 8), 128, 256),
+                              ([8192, 100], (8, 2), 128, 256), ([1024] * 32, (28, 4), 128, 256),
+                              ([1024] * 32, (64, 8), 128, 128), ([131072], (32, 8), 128, 256),
+                              ([65536], (8, 2), 64, 128), ([1024] * 32, (64, 8), 64, 128),
+                              ([1024] * 32, (32, 8), 64, 256), ([4096] * 8, (32, 8), 64, 128),
+                              ([4096] * 8, (14, 2), 64, 256), ([8192] * 4, (14, 2), 64, 128),
+                              ([300], (14, 2), 64, 256)):
         n = [8 if s > 100000 else 1 for s in S]
-        plan = B.skrull_attn_plan(S, n, [0] * len(S), 8, 2, d, d ** -0.5)
-        assert plan.info.wg_query_rows == want, (S, d)
+        plan = B.skrull_attn_plan(S, n, [0] * len(S), heads[0], heads[1], d, d ** -0.5)
+        assert plan.info.wg_query_rows == want, (S, heads, d)
         plan.destroy()
-        plan = B.skrull_attn_plan(S, n, [0] * len(S), 8, 2, d, d ** -0.5, wg_query_rows=384 - want)
+        plan = B.skrull_attn_plan(S, n, [0] * len(S), heads[0], heads[1], d, d ** -0.5, wg_query_rows=384 - want)
         assert plan.info.wg_query_rows == 384 - want
         plan.destroy()
 
