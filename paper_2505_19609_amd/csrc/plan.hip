@@ -67,13 +67,17 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
     const int t = threadIdx.x;
     if (t == 0) first_bad = 0x7fffffff;
     __syncthreads();
-    // Choice between BN and a larger dK/dV block bn_alt (0 = no choice to make): the larger
+    // Choice between BN and a larger dK/dV block bn_alt (0 = no choice to make).  The larger
     // one is taken when, with blocks of BN key rows, the costliest work item exceeds an even
     // share of the whole list over the compute units (cost_max > cost_sum * Hkv / CUs), the
-    // same ratio that decides the head split.  The costs are those of the dK/dV items that
-    // plan_emit_kernel would write for BN.
+    // same ratio that decides the head split; the costs are those of the dK/dV items that
+    // plan_emit_kernel would write for BN.  It is also taken when the list of larger blocks is
+    // still long: at least five of them (x KV heads) per compute unit and a sequence of at least
+    // two of them.  Fewer, larger workgroups run the rounds 7-15 % faster (measured on 16 to 64
+    // heads x 32,768 tokens, uniform and ragged lengths) but balance worse, and below about five
+    // items per unit a ragged micro-batch lost 4-13 % by them.
     if (bn_alt != 0) {
-        int64_t c_sum = 0, c_max = 0;
+        int64_t c_sum = 0, c_max = 0, n_alt = 0, longest = 0;
         for (int32_t k = t; k < K; k += kScanThreads) {
             const int64_t s = S[k], n = N[k], r = R[k], z = Z[k];
             const int64_t chunks = n * (z ? 2 : 1);
@@ -85,6 +89,8 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
                 qb[part] = (idx[part] * s) / chunks;
                 qe[part] = ((idx[part] + 1) * s) / chunks;
             }
+            n_alt += ceil_div64(qe[nseg - 1], bn_alt);
+            longest = qe[nseg - 1] > longest ? qe[nseg - 1] : longest;
             for (int64_t j0 = 0; j0 < qe[nseg - 1]; j0 += BN) {
                 int64_t cost = 0;
                 for (int part = 0; part < nseg; ++part) {
@@ -108,7 +114,19 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
         }
         c_max = lds[0];
         __syncthreads();
-        if (c_max * compute_units > c_sum * kv_heads) BN = bn_alt;
+        block_exclusive_scan(n_alt, lds, &tot);
+        n_alt = tot;
+        lds[t] = longest;
+        __syncthreads();
+        for (int off = kScanThreads / 2; off > 0; off >>= 1) {
+            if (t < off && lds[t + off] > lds[t]) lds[t] = lds[t + off];
+            __syncthreads();
+        }
+        longest = lds[0];
+        __syncthreads();
+        if (c_max * compute_units > c_sum * kv_heads ||
+            (n_alt * kv_heads >= 5 * (int64_t)compute_units && longest >= 2 * (int64_t)bn_alt))
+            BN = bn_alt;
     }
     int64_t base_s = 0, base_q = 0, base_k = 0, base_f = 0, base_d = 0, pairs = 0;
     for (int32_t k0 = 0; k0 < K; k0 += kScanThreads) {
