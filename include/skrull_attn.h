@@ -134,10 +134,11 @@ enum {
  * Tuning fields left at 0 are chosen by the library from the head shape, the
  * lengths and the device's compute-unit count, and skrull_attn_plan_info
  * reports what is in effect: block_n is 128, or 192 at head_dim 64 when a
- * sequence of 8,192 tokens or more is present, when the work list is short, or
- * when it is long enough for fewer, larger items (five blocks of 192 key rows
- * x KV heads per compute unit; the dK/dV kernel then runs 12 wavefronts over
- * 192 key rows); head_split above 1
+ * sequence of 8,192 tokens or more is present, when the work list is short
+ * (its costliest item above an even share per compute unit), or when fewer,
+ * larger items still balance (five blocks of 192 key rows x KV heads per
+ * compute unit, or a costliest item under 0.7 of the even share; the dK/dV
+ * kernel then runs 12 wavefronts over 192 key rows); head_split above 1
  * when the longest dK/dV chain exceeds an even share of the work list;
  * wg_query_rows 128 when the micro-batch holds enough work for the smaller
  * workgroups to pay (head_dim 64: at least 24 blocks of 256 query rows x heads

@@ -290,17 +290,23 @@ int skrull_attn_plan(const skrull_attn_problem_t *p, void *hip_stream, skrull_at
         // every batch measured from 2 x 8,192 to 65,536 tokens was 7-50 % faster split 7 ways
         // (65,536 tokens, ratio 0.75: 17.4 -> 16.1 ms; eight 8,192-token sequences, 0.72: equal).
         const double share = (double)totals.dkv_cost_sum * plan->Hkv / (double)compute_units;
-        // (that factor of two only where the list is short, under five items x KV heads per compute
-        // unit; with longer lists of 192-key items, 16-64 heads on ragged 32,768-token micro-batches,
-        // a split at ratios of 0.6-0.9 cost 6-16 %)
+        // (that factor of two only where it was measured to pay: a sequence of 8,192 tokens or more
+        // and a short list, under five items x KV heads per compute unit; with longer lists of
+        // 192-key items, 16-64 heads on ragged 32,768-token micro-batches, a split at ratios of
+        // 0.6-0.9 cost 6-16 %, and on short lists of short sequences up to 90 %)
         const bool short_list = (int64_t)totals.n_dkv * plan->Hkv < 5 * (int64_t)compute_units;
-        const double scale = (plan->d == 64 && plan->BN == 192 && short_list) ? 2.0 : 1.0;
+        const double scale = (plan->d == 64 && plan->BN == 192 && short_list && longest_seq >= 8192) ? 2.0 : 1.0;
         const double want = share > 0.0 ? scale * (double)totals.dkv_cost_max / share : 1.0;
         int32_t hs = want <= 1.0 ? 1 : (want >= (double)group ? group : (int32_t)ceil(want));
         // only equal shares: workgroups with different numbers of heads walk the query
         // tiles at different paces, stop sharing them in L2 and run 10 % slower (measured
         // with 7 heads per group split 3 + 4), so take the next divisor of the group size
+        const int32_t asked = hs;
         while (hs < group && group % hs != 0) ++hs;
+        // ... unless that divisor is three times what was asked for and the chain is less than
+        // 1.5 even shares (7 heads per group at ratios of 1.0-1.4: split 7 ways 6-14 % slower
+        // than unsplit, equal at 1.7)
+        if (hs >= 3 * asked && want < 1.5) hs = 1;
         plan->head_split = hs < 1 ? 1 : (hs > group ? group : hs);
     }
     rc = SKRULL_OK;

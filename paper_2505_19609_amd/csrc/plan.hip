@@ -71,11 +71,12 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
     // one is taken when, with blocks of BN key rows, the costliest work item exceeds an even
     // share of the whole list over the compute units (cost_max > cost_sum * Hkv / CUs), the
     // same ratio that decides the head split; the costs are those of the dK/dV items that
-    // plan_emit_kernel would write for BN.  It is also taken when the list of larger blocks is
-    // still long: at least five of them (x KV heads) per compute unit and a sequence of at least
-    // two of them.  Fewer, larger workgroups run the rounds 7-15 % faster (measured on 16 to 64
-    // heads x 32,768 tokens, uniform and ragged lengths) but balance worse, and below about five
-    // items per unit a ragged micro-batch lost 4-13 % by them.
+    // plan_emit_kernel would write for BN.  It is also taken, given a sequence of at least two
+    // of the larger blocks, when their list is still long (at least five x KV heads per compute
+    // unit) or when the costliest item stays under 0.7 of that even share.  Fewer, larger
+    // workgroups run the rounds 7-18 % faster (measured on 14 to 64 heads x 16,384-65,536 tokens,
+    // uniform and ragged lengths) but balance worse: with few items and a costliest one between
+    // 0.7 and 1.0 of the even share, ragged micro-batches lost 4-15 % by them.
     if (bn_alt != 0) {
         int64_t c_sum = 0, c_max = 0, n_alt = 0, longest = 0;
         for (int32_t k = t; k < K; k += kScanThreads) {
@@ -124,8 +125,10 @@ __global__ __launch_bounds__(kScanThreads) void plan_ranges_kernel(
         }
         longest = lds[0];
         __syncthreads();
+        const bool long_list = n_alt * kv_heads >= 5 * (int64_t)compute_units;
+        const bool even_list = 10 * c_max * compute_units <= 7 * c_sum * kv_heads;
         if (c_max * compute_units > c_sum * kv_heads ||
-            (n_alt * kv_heads >= 5 * (int64_t)compute_units && longest >= 2 * (int64_t)bn_alt))
+            ((long_list || even_list) && longest >= 2 * (int64_t)bn_alt))
             BN = bn_alt;
     }
     int64_t base_s = 0, base_q = 0, base_k = 0, base_f = 0, base_d = 0, pairs = 0;

@@ -789,11 +789,13 @@ def test_dkv_block_is_chosen_from_head_dim_and_shape_of_the_work():
     plan = B.skrull_attn_plan([16384], [1], [0], 14, 2, 64, 0.125, block_n=128)
     assert plan.block_n == 128
     plan.destroy()
-    # ... or long enough for fewer, larger items: five blocks of 192 key rows x KV heads per
-    # compute unit (256 units) and a sequence of at least 384 tokens
-    for S, heads, want in (([1024] * 32, (32, 8), 192), ([1024] * 27, (32, 8), 192), ([1024] * 26, (32, 8), 128),
+    # ... or when fewer, larger items still balance: five blocks of 192 key rows x KV heads per
+    # compute unit (256 units), or a costliest 128-key item under 0.7 of the even share, and a
+    # sequence of at least 384 tokens.  (Config 2's lengths with 8 KV heads: ratio 0.86, 760 items.)
+    for S, heads, want in (([1024] * 32, (32, 8), 192), ([1024] * 26, (32, 8), 192),
                            ([256] * 128, (32, 8), 128), ([383] * 100, (16, 16), 128), ([384] * 100, (16, 16), 192),
-                           ([1024] * 32, (32, 4), 128)):
+                           ([1024] * 32, (32, 4), 192), (list(W.config(2).seq_len), (32, 8), 128),
+                           (list(W.config(2).seq_len) * 2, (32, 8), 192)):
         plan = B.skrull_attn_plan(S, [1] * len(S), [0] * len(S), heads[0], heads[1], 64, 0.125)
         assert plan.block_n == want, (S[:2], len(S), heads, plan.block_n)
         plan.destroy()
