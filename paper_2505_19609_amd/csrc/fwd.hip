@@ -227,7 +227,6 @@ __device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
             }
         }
         SB();
-        const float m_new = row_max(s_in);
         float rs0 = 0.0f, rs1 = 0.0f;
         uint32_t pw[8];
         SB();
@@ -247,7 +246,7 @@ __device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
             }
 #pragma unroll
             for (int e = 0; e < EPS; e += 2)
-                softmax_exp2(s_in[EPS * i + e], s_in[EPS * i + e + 1], cs, m_new, t[e], t[e + 1]);
+                softmax_exp2(s_in[EPS * i + e], s_in[EPS * i + e + 1], cs, m_run, t[e], t[e + 1]);
             SB();
             oacc[i % TT] = mfma32(vf[i % 4], p_in[i / TT], oacc[i % TT]);
 #pragma unroll
@@ -262,10 +261,37 @@ __device__ __forceinline__ void fwd_work(const FwdParams &prm, const int bid)
             }
             SB();
         }
-        const float rs = rs0 + rs1;
+        float rs = rs0 + rs1;
+        // The step took its exponentials against the bound of the steps before it, without
+        // looking for the maximum of its scores first (that chain of maxima was a seventh of the
+        // step's vector instructions).  The bound only has to hold loosely, and the sum the step
+        // forms anyway tells when it no longer does: a row whose probabilities of this step add up
+        // to more than 2^10 in either half of the wavefront (or overflowed) takes its true
+        // maximum as the new bound, and the step's probabilities are formed again from the
+        // scores, which are still in their registers.  After the first tiles this hardly ever
+        // happens; rows that keep their bound form the same values again.
+        constexpr float kSumBound = 1024.0f;
+        float m_new = m_run;
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumBound)) != 0) {
+            float mx = fmaxf(s_in[0], s_in[1]);
+#pragma unroll
+            for (int v = 2; v < 16; v += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s_in[v]), s_in[v + 1]);
+            mx = max_halves(mx) * cs;
+            const bool moved = !(max_halves(rs) <= kSumBound);
+            m_new = moved ? fmaxf(mx, m_run) : m_run;
+            rs0 = 0.0f;
+            rs1 = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                float t0, t1;
+                softmax_exp2(s_in[v], s_in[v + 1], cs, m_new, t0, t1);
+                pw[v >> 1] = softmax_sum_pack(t0, t1, rs0, rs1);
+            }
+            rs = rs0 + rs1;
+        }
+        finish(m_new, rs);
         p_out[0] = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
         p_out[1] = as_bf16x8(make_uint4(pw[4], pw[5], pw[6], pw[7]));
-        finish(m_new, rs);
     };
 
     // ---- plain step j with run-time guards (start, end and diagonal of the wave's range)

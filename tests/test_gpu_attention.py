@@ -153,7 +153,7 @@ def test_extreme_logits(oracle, scale, d):
     """Scores far outside the usual range: with softmax_scale 1 (0.75) on N(0,1) data of
     head_dim 64 (128) they have a standard deviation of 8 and single rows reach +-40,
     so probabilities span e^80 and the running maximum has to move; with 0.002 the
-    softmax is almost uniform.  (The forward lets the running maximum lag by up to 2^8.)"""
+    softmax is almost uniform.  (The forward's bound on the scores of a row may lag behind them by up to 2^10.)"""
     w = W.Workload(f"logits{scale}", [700, 1300, 64], [1, 1, 1], [0, 0, 0], 4, 2, d, scale, 4242)
     out = run_library(w)
     f = widen(out["vals"])
@@ -723,6 +723,41 @@ def test_head_split_is_chosen_from_the_work_list():
         p = B.skrull_attn_plan(S, [1] * len(S), [0] * len(S), hq, hkv, d, d ** -0.5, block_n=128)   # r is for 128-key items
         assert p.head_split == want, (S, hq, hkv, p.head_split)
         p.destroy()
+
+
+@pytest.mark.parametrize("d,wg", [(64, 128), (64, 256), (128, 128), (128, 256)])
+@pytest.mark.parametrize("jump", [12.0, 60.0, 100.0])
+def test_forward_bound_follows_late_jumps(oracle, d, wg, jump):
+    """The pipelined forward step takes its exponentials against the bound of the steps before and
+    notices from their sum that the bound no longer holds.  Here a few keys deep inside long rows
+    score `jump` (natural units after scaling) above everything before them for a set of query
+    rows: 2^17 above the bound (sum far over its limit), 2^87, and 2^144 (the exponential
+    overflows before the step is redone).  Other rows see the same keys with ordinary scores."""
+    S = [2300, 1100]
+    w = W.Workload(f"jump{jump}_{d}_{wg}", S, [1, 1], [0, 0], 4, 2, d, d ** -0.5, 606)
+    from paper_2505_19609_amd import binding as B
+    probe = B.skrull_attn_plan(S, [1, 1], [0, 0], 4, 2, d, w.softmax_scale)
+    vals = W.make_values(w, probe.total_q, probe.total_k)
+    probe.destroy()
+    f = widen(vals)
+    u = np.full(d, d ** -0.5, np.float32)                   # unit vector
+    hot_keys = [1500, 1501, 1533, 2111, 2300 + 700]         # packed key rows (both sequences)
+    hot_rows = list(range(1600, 1700, 7)) + [2200, 2299, 2300 + 900, 2300 + 1099]
+    a = 8.0
+    for j in hot_keys:
+        f["k"][j, :, :] = (jump * d ** 0.5 / a) * u         # q.k * scale = jump for the hot rows
+    for i in hot_rows:
+        f["q"][i, :, :] = a * u
+    vals = {n: W.f32_to_bf16_bits(x) for n, x in f.items()}
+    out = run_library(w, vals=vals, wg_query_rows=wg)
+    f = widen(out["vals"])
+    desc = oracle.ranges(S, [1, 1], [0, 0])
+    O, LSE = oracle.attention_fwd(f["q"], f["k"], f["v"], desc, w.softmax_scale)
+    _report("O", out["o"], O, TOL_O)
+    # LSE itself reaches `jump` here: a relative bound beside the absolute one (fp32 output)
+    _report("LSE", out["lse"], LSE, TOL_O, rtol=1e-5)
+    assert np.isfinite(out["dq"]).all() and np.isfinite(out["dk"]).all() and np.isfinite(out["dv"]).all()
+    out["plan"].destroy()
 
 
 @pytest.mark.parametrize("rows", [128, 256])
