@@ -445,36 +445,41 @@ __global__ __launch_bounds__(64 * NWQ, 2) void dq_kernel(const BwdParams prm)
 // moved to its first use, behind all of them, and a wave that issues nothing but
 // vector instructions for a long stretch slows the MFMAs of the wave it shares a
 // SIMD with).
-// Four scores -> four probabilities exp2(s * c - l), packed to two bf16 pairs.  Every
-// exponential has an instruction between it and the first use of its result.
-__device__ __forceinline__ void p_quad(const float (&sv)[4], float c, const float4 &l, uint32_t &w0, uint32_t &w1)
+// Four scores -> four probabilities exp2(s * c - l), packed twice: to two bf16 pairs (w0, w1:
+// the S wave's own MFMA operand) and to two fp16 pairs (h0, h1: what the dP wave gets).  The
+// dP wave only multiplies P element by element, and a mixed-precision multiply takes an fp16
+// operand as it is, where a bf16 one costs an instruction to widen first: the extra packing
+// here is on the wave of the pair that waits at the barrier, the widening was on the one that
+// does not.  (Probabilities are at most 1; fp16 keeps three bits more of them than bf16 and
+// goes to zero below 6e-8.)  Every exponential has an instruction between it and the first use
+// of its result.
+__device__ __forceinline__ void p_quad(const float (&sv)[4], float c, const float4 &l, uint32_t &w0, uint32_t &w1,
+                                       uint32_t &h0, uint32_t &h1)
 {
     float t0, t1, t2, t3;
-    asm volatile("v_fma_f32 %0, %6, %10, -%11\n\t"
-                 "v_fma_f32 %1, %7, %10, -%12\n\t"
-                 "v_fma_f32 %2, %8, %10, -%13\n\t"
-                 "v_fma_f32 %3, %9, %10, -%14\n\t"
+    asm volatile("v_fma_f32 %0, %8, %12, -%13\n\t"
+                 "v_fma_f32 %1, %9, %12, -%14\n\t"
+                 "v_fma_f32 %2, %10, %12, -%15\n\t"
+                 "v_fma_f32 %3, %11, %12, -%16\n\t"
                  "v_exp_f32 %0, %0\n\t"
                  "v_exp_f32 %1, %1\n\t"
                  "v_exp_f32 %2, %2\n\t"
                  "v_exp_f32 %3, %3\n\t"
                  "v_cvt_pk_bf16_f32 %4, %0, %1\n\t"
-                 "v_cvt_pk_bf16_f32 %5, %2, %3"
-                 : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(w0), "=&v"(w1)
+                 "v_cvt_pk_bf16_f32 %5, %2, %3\n\t"
+                 "v_cvt_pk_f16_f32 %6, %0, %1\n\t"
+                 "v_cvt_pk_f16_f32 %7, %2, %3"
+                 : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(w0), "=&v"(w1), "=&v"(h0), "=&v"(h1)
                  : "v"(sv[0]), "v"(sv[1]), "v"(sv[2]), "v"(sv[3]), "s"(c), "v"(l.x), "v"(l.y), "v"(l.z), "v"(l.w));
 }
-// Two packed bf16 P pairs times four (dP - D) values -> two packed bf16 dS pairs.
+// Two packed fp16 P pairs times four (dP - D) values -> two packed bf16 dS pairs.
 __device__ __forceinline__ void ds_quad(uint32_t p01, uint32_t p23, const float (&g)[4], uint32_t &w0, uint32_t &w1)
 {
     float t0, t1, t2, t3;
-    asm volatile("v_lshlrev_b32 %0, 16, %6\n\t"
-                 "v_and_b32 %1, 0xffff0000, %6\n\t"
-                 "v_lshlrev_b32 %2, 16, %7\n\t"
-                 "v_and_b32 %3, 0xffff0000, %7\n\t"
-                 "v_mul_f32 %0, %0, %8\n\t"
-                 "v_mul_f32 %1, %1, %9\n\t"
-                 "v_mul_f32 %2, %2, %10\n\t"
-                 "v_mul_f32 %3, %3, %11\n\t"
+    asm volatile("v_fma_mix_f32 %0, %6, %8, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]\n\t"
+                 "v_fma_mix_f32 %1, %6, %9, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
+                 "v_fma_mix_f32 %2, %7, %10, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]\n\t"
+                 "v_fma_mix_f32 %3, %7, %11, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
                  "v_cvt_pk_bf16_f32 %4, %0, %1\n\t"
                  "v_cvt_pk_bf16_f32 %5, %2, %3"
                  : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(w0), "=&v"(w1)
@@ -684,6 +689,7 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
             // S of the second 32 rows with the probabilities of the first behind its
             // MFMAs, then dV of the first with the probabilities of the second
             uint32_t w[2][8];
+            uint32_t hw[4];  // fp16 copies of two quads at a time, on their way to the dP wave
             bf16x8 ft[4];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -701,7 +707,8 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
                     const int vb = KS == 8 ? ks / 2 : ks;
                     const float4 l4 = *(const float4 *)(t_lse + 8 * vb + 4 * h);
                     const float sv[4] = {s[0][4 * vb], s[0][4 * vb + 1], s[0][4 * vb + 2], s[0][4 * vb + 3]};
-                    p_quad(sv, cs, l4, w[0][2 * vb], w[0][2 * vb + 1]);
+                    p_quad(sv, cs, l4, w[0][2 * vb], w[0][2 * vb + 1], hw[2 * (vb & 1)], hw[2 * (vb & 1) + 1]);
+                    if (vb & 1) *(uint4 *)(px + (vb >> 1) * 1024 + lane * 16) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
                 }
                 if (ks >= KS - 3) ft[(ks - (KS - 3))] = fa.cols(tdo, (ks - (KS - 3)) % TT, (ks - (KS - 3)) / TT);
                 SB();
@@ -709,8 +716,6 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
             if (need_mask) mask_block(s[1], 1);
             const bf16x8 pb0 = as_bf16x8(make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
             const bf16x8 pb1 = as_bf16x8(make_uint4(w[0][4], w[0][5], w[0][6], w[0][7]));
-            *(bf16x8 *)(px + 0 * 1024 + lane * 16) = pb0;
-            *(bf16x8 *)(px + 1 * 1024 + lane * 16) = pb1;
             // dV of rows 0..31 (2 x TT MFMAs); probabilities of rows 32..63 behind them
 #pragma unroll
             for (int m = 0; m < 2 * TT; ++m) {
@@ -721,14 +726,13 @@ __device__ __forceinline__ void dkv_work(const BwdParams &prm, const int bid)
                     const int vb = TT == 4 ? m / 2 : m;
                     const float4 l4 = *(const float4 *)(t_lse + 32 + 8 * vb + 4 * h);
                     const float sv[4] = {s[1][4 * vb], s[1][4 * vb + 1], s[1][4 * vb + 2], s[1][4 * vb + 3]};
-                    p_quad(sv, cs, l4, w[1][2 * vb], w[1][2 * vb + 1]);
+                    p_quad(sv, cs, l4, w[1][2 * vb], w[1][2 * vb + 1], hw[2 * (vb & 1)], hw[2 * (vb & 1) + 1]);
+                    if (vb & 1) *(uint4 *)(px + (2 + (vb >> 1)) * 1024 + lane * 16) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
                 }
                 SB();
             }
             const bf16x8 pb2 = as_bf16x8(make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
             const bf16x8 pb3 = as_bf16x8(make_uint4(w[1][4], w[1][5], w[1][6], w[1][7]));
-            *(bf16x8 *)(px + 2 * 1024 + lane * 16) = pb2;
-            *(bf16x8 *)(px + 3 * 1024 + lane * 16) = pb3;
             // dV of rows 32..63
 #pragma unroll
             for (int m = 2 * TT; m < 4 * TT; ++m) {
